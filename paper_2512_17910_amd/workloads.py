@@ -1,0 +1,286 @@
+"""Seeded synthetic inputs for the masked multi-adapter aLoRA QKV projection.
+
+This module only *draws* data: token batches, weights, adapter factors, activation
+points and paged-cache slot maps shaped like the paper's multi-turn, multi-adapter
+pipelines (random prompts and random adapters, Sec. 4.1; long cached context with a
+short activated tail, Sec. 4.2; several adapters per batch, Sec. 4.4.1).  It holds
+none of the method's arithmetic: no projection, no mask, no grouping.  Both the CPU
+oracle's tests and the HIP path's tests/benchmark take their inputs from here and
+nothing else is shared between the two.
+
+Values are drawn with numpy's counter-based Philox generator, keyed by
+(seed, stream), so every array is reproducible independently of the others.
+bf16 arrays are carried as uint16 bit patterns (round-to-nearest-even from fp32).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+SEED = 0x2512_1791_0A10_4A5D  # one fixed 64-bit constant; streams select the array
+
+# stream ids (second half of the Philox key)
+_ST_X, _ST_W, _ST_A, _ST_B, _ST_STRUCT, _ST_SLOTS, _ST_CACHE = 1, 2, 3, 4, 5, 6, 7
+
+
+# --------------------------------------------------------------------------------------
+# storage-format helpers (bit manipulation only)
+# --------------------------------------------------------------------------------------
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns -> the exactly equal fp32 values."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def widen_f64(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Storage array (fp32 values, or bf16 bit patterns) -> exactly equal fp64 values."""
+    if dtype == "bf16":
+        return bf16_bits_to_f32(a).astype(np.float64)
+    return np.asarray(a, dtype=np.float32).astype(np.float64)
+
+
+def _rng(seed: int, stream: int, sub: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[seed & (2**64 - 1), (stream << 32) | sub]))
+
+
+def _normal(seed: int, stream: int, sub: int, shape, std: float, dtype: str) -> np.ndarray:
+    g = _rng(seed, stream, sub)
+    a = g.standard_normal(size=shape, dtype=np.float32)
+    a *= np.float32(std)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(a)
+    return a
+
+
+# --------------------------------------------------------------------------------------
+# the workload container
+# --------------------------------------------------------------------------------------
+@dataclass
+class Segment:
+    """One (adapter, activation point) unit: the paper's 'request' (App. B)."""
+    seq: int               # which sequence's block table the tokens use
+    first_pos: int         # absolute position of the segment's first projected token
+    n_tokens: int
+    adapter: int           # -1 = base model request
+    activation_start: int  # absolute position; >= first_pos + n_tokens means never active
+
+
+@dataclass
+class Workload:
+    name: str
+    dtype: str             # "f32" | "bf16"
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    n_adapters: int
+    rank: int
+    block_size: int
+    n_slots: int
+    segments: List[Segment]
+    x: np.ndarray = None                   # [T, hidden]
+    W: np.ndarray = None                   # [hidden, N]
+    A: List[np.ndarray] = field(default_factory=list)   # each [hidden, rank]
+    B: List[np.ndarray] = field(default_factory=list)   # each [rank, N]
+    token_adapter_ids: np.ndarray = None   # int32 [T]
+    token_seg_ids: np.ndarray = None       # int32 [T]
+    token_positions: np.ndarray = None     # int32 [T]
+    activation_start: np.ndarray = None    # int32 [G]
+    slot_mapping: np.ndarray = None        # int64 [T]
+    cached_prefix_slots: Optional[np.ndarray] = None  # slots of skipped, already cached prefixes
+
+    @property
+    def T(self) -> int:
+        return int(self.token_adapter_ids.shape[0])
+
+    @property
+    def Nq(self) -> int:
+        return self.n_q_heads * self.head_dim
+
+    @property
+    def Nkv(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+    @property
+    def N(self) -> int:
+        return self.Nq + 2 * self.Nkv
+
+    @property
+    def n_segments(self) -> int:
+        return int(self.activation_start.shape[0])
+
+    @property
+    def elem_bytes(self) -> int:
+        return 2 if self.dtype == "bf16" else 4
+
+
+def cache_fill(n_slots: int, width: int, dtype: str, which: int, seed: int = SEED) -> np.ndarray:
+    """Pre-existing cache contents ("someone else's blocks"): small seeded finite values."""
+    g = _rng(seed, _ST_CACHE, which)
+    a = g.standard_normal(size=(n_slots, width), dtype=np.float32)
+    a *= np.float32(0.25)
+    return f32_to_bf16_bits(a) if dtype == "bf16" else a
+
+
+def assemble(name: str, dtype: str, hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+             n_adapters: int, rank: int, block_size: int, segments: Sequence[Segment],
+             seq_max_len: Sequence[int], seed: int = SEED, extra_blocks: int = 0,
+             weight_key: int = 0, pad_rows: Sequence[int] = (),
+             x_std: float = 1.0, with_values: bool = True) -> Workload:
+    """Lay segments out as one flattened token batch and draw values.
+
+    seq_max_len[s] fixes how many cache blocks sequence s owns (ceil(len/block_size));
+    physical block ids are a seeded permutation of all blocks (+extra_blocks spare ones).
+    pad_rows: token rows that become padding (adapter -1, slot -1) after layout.
+    """
+    Nq, Nkv = n_q_heads * head_dim, n_kv_heads * head_dim
+    N = Nq + 2 * Nkv
+    blocks_per_seq = [(int(m) + block_size - 1) // block_size for m in seq_max_len]
+    n_blocks = int(sum(blocks_per_seq)) + int(extra_blocks)
+    perm = _rng(seed, _ST_SLOTS).permutation(n_blocks).astype(np.int64)
+    tables, o = [], 0
+    for nb in blocks_per_seq:
+        tables.append(perm[o:o + nb])
+        o += nb
+
+    aid, seg, pos, slot, starts = [], [], [], [], []
+    for g, s in enumerate(segments):
+        p = np.arange(s.first_pos, s.first_pos + s.n_tokens, dtype=np.int64)
+        aid.append(np.full(s.n_tokens, s.adapter, dtype=np.int32))
+        seg.append(np.full(s.n_tokens, g, dtype=np.int32))
+        pos.append(p.astype(np.int32))
+        slot.append(tables[s.seq][p // block_size] * block_size + p % block_size)
+        starts.append(s.activation_start)
+    cat = lambda l, dt: (np.concatenate(l).astype(dt) if l else np.zeros(0, dt))
+    w = Workload(name=name, dtype=dtype, hidden=hidden, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                 head_dim=head_dim, n_adapters=n_adapters, rank=rank, block_size=block_size,
+                 n_slots=n_blocks * block_size, segments=list(segments))
+    w.token_adapter_ids = cat(aid, np.int32)
+    w.token_seg_ids = cat(seg, np.int32)
+    w.token_positions = cat(pos, np.int32)
+    w.slot_mapping = cat(slot, np.int64)
+    w.activation_start = np.asarray(starts, dtype=np.int32).reshape(-1)
+    for r in pad_rows:
+        w.token_adapter_ids[r] = -1
+        w.slot_mapping[r] = -1
+    w._tables = tables
+    if with_values:
+        T = w.T
+        w.x = _normal(seed, _ST_X, 0, (T, hidden), x_std, dtype)
+        wk = weight_key if weight_key else seed
+        w.W = _normal(wk, _ST_W, 0, (hidden, N), hidden ** -0.5, dtype)
+        w.A = [_normal(wk, _ST_A, i, (hidden, rank), hidden ** -0.5, dtype) for i in range(n_adapters)]
+        w.B = [_normal(wk, _ST_B, i, (rank, N), rank ** -0.5, dtype) for i in range(n_adapters)]
+    return w
+
+
+# --------------------------------------------------------------------------------------
+# the five benchmark configurations
+# --------------------------------------------------------------------------------------
+_W8B = SEED ^ 0x8B8B8B8B      # weights shared by every 8B-shaped config
+_W70B = SEED ^ 0x70707070
+
+
+def config1(seed: int = SEED, with_values: bool = True) -> Workload:
+    """Tiny fp32 layer: 2 sequences x 32 tokens, activation at 24 and at 32 (never)."""
+    segs = [Segment(0, 0, 32, 0, 24), Segment(1, 0, 32, 1, 32)]
+    return assemble("cfg1-tiny-f32", "f32", 256, 4, 2, 64, 2, 8, 16, segs, [32, 32],
+                    seed=seed ^ 1, extra_blocks=4, with_values=with_values)
+
+
+def config2(seed: int = SEED, with_values: bool = True) -> Workload:
+    """Llama-3-8B-shaped prefill chunk: 8 sequences x 512 tokens, 8 rank-32 adapters."""
+    g = _rng(seed ^ 2, _ST_STRUCT)
+    segs = []
+    for s in range(8):
+        segs.append(Segment(s, 0, 512, int(g.integers(0, 8)), int(g.integers(256, 512))))
+    return assemble("cfg2-8b-prefill", "bf16", 4096, 32, 8, 128, 8, 32, 16, segs, [512] * 8,
+                    seed=seed ^ 2, weight_key=_W8B, with_values=with_values)
+
+
+def config3(seed: int = SEED, with_values: bool = True) -> Workload:
+    """Llama-3-8B-shaped decode: 256 sequences x 1 token, 16 adapters, 25% base-only rows."""
+    g = _rng(seed ^ 3, _ST_STRUCT)
+    base_rows = set(g.permutation(256)[:64].tolist())
+    segs = []
+    for s in range(256):
+        p = int(g.integers(1, 2048))
+        a = int(g.integers(0, 16))
+        st = int(g.integers(0, p + 1))
+        segs.append(Segment(s, p, 1, -1 if s in base_rows else a, st))
+    return assemble("cfg3-8b-decode", "bf16", 4096, 32, 8, 128, 16, 32, 16, segs, [2048] * 256,
+                    seed=seed ^ 3, weight_key=_W8B, with_values=with_values)
+
+
+def config4(seed: int = SEED, with_values: bool = True) -> Workload:
+    """Llama-3-70B-shaped prefill: 4 sequences x 2048 tokens, 4 rank-64 adapters, late activation."""
+    g = _rng(seed ^ 4, _ST_STRUCT)
+    segs = [Segment(s, 0, 2048, int(g.integers(0, 4)), int(g.integers(1844, 2048))) for s in range(4)]
+    return assemble("cfg4-70b-prefill", "bf16", 8192, 64, 8, 128, 4, 64, 16, segs, [2048] * 4,
+                    seed=seed ^ 4, weight_key=_W70B, with_values=with_values)
+
+
+def config5(seed: int = SEED, with_values: bool = True) -> Workload:
+    """Long-context multi-turn mix on 8B shapes: 4 x 16384-token sequences whose base-aligned
+    prefix (a multiple of 16 tokens, 60-90% of the sequence) is already cached and skipped;
+    each projected suffix holds 1-3 (adapter, activation point) segments."""
+    g = _rng(seed ^ 5, _ST_STRUCT)
+    segs, prefix = [], []
+    for s in range(4):
+        pre = 16 * int(g.integers(615, 922))
+        prefix.append(pre)
+        n_seg = int(g.integers(1, 4))
+        cuts = sorted(int(c) for c in g.choice(np.arange(pre + 64, 16384 - 64), size=n_seg - 1, replace=False))
+        bounds = [pre] + cuts + [16384]
+        for b0, b1 in zip(bounds[:-1], bounds[1:]):
+            segs.append(Segment(s, b0, b1 - b0, int(g.integers(0, 32)), int(g.integers(b0, b1))))
+    w = assemble("cfg5-8b-longctx", "bf16", 4096, 32, 8, 128, 32, 16, 16, segs, [16384] * 4,
+                 seed=seed ^ 5, weight_key=_W8B, with_values=with_values)
+    pre_slots = []
+    for s in range(4):
+        p = np.arange(0, prefix[s], dtype=np.int64)
+        pre_slots.append(w._tables[s][p // 16] * 16 + p % 16)
+    w.cached_prefix_slots = np.concatenate(pre_slots)
+    return w
+
+
+CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+
+
+def small_mixed(dtype: str = "bf16", hidden: int = 256, n_q_heads: int = 4, n_kv_heads: int = 2,
+                head_dim: int = 64, n_adapters: int = 3, rank: int = 16, block_size: int = 16,
+                seq_lens: Sequence[int] = (150, 37, 1, 90), seed: int = 7, pad_every: int = 0,
+                x_std: float = 1.0) -> Workload:
+    """A small heterogeneous batch for parity tests: ragged sequence lengths, every kind of
+    request (base-only, standard LoRA = activation at 0, aLoRA activated mid-sequence,
+    aLoRA never activated), optional padding rows, spare cache blocks."""
+    g = _rng(SEED ^ seed, _ST_STRUCT)
+    segs = []
+    kinds = ["alora", "lora", "base", "never"]
+    for s, n in enumerate(seq_lens):
+        kind = kinds[s % 4]
+        first = int(g.integers(0, 40))
+        a = int(g.integers(0, n_adapters))
+        if kind == "base":
+            segs.append(Segment(s, first, n, -1, 0))
+        elif kind == "lora":
+            segs.append(Segment(s, first, n, a, 0))
+        elif kind == "never":
+            segs.append(Segment(s, first, n, a, first + n))
+        else:
+            segs.append(Segment(s, first, n, a, first + int(g.integers(0, max(n, 1)))))
+    T = sum(seq_lens)
+    pads = list(range(pad_every - 1, T, pad_every)) if pad_every else []
+    return assemble(f"small-{dtype}-{seed}", dtype, hidden, n_q_heads, n_kv_heads, head_dim,
+                    n_adapters, rank, block_size, segs,
+                    [s.first_pos + s.n_tokens for s in segs], seed=SEED ^ seed,
+                    extra_blocks=5, pad_rows=pads, x_std=x_std)
