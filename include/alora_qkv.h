@@ -1,0 +1,165 @@
+/*
+ * alora_qkv.h - C ABI of the MI355X (gfx950) library for the activation-aware masked
+ * multi-adapter QKV projection with paged K/V write used when serving Activated LoRA
+ * (aLoRA) adapters beside their base model.
+ *
+ * What one call computes (paper Sec. 2.3 block equations; Algorithm 1; App. B mask):
+ *
+ *   active(t) = token_adapter_ids[t] >= 0  and
+ *               token_positions[t] >= activation_start[token_seg_ids[t]]
+ *   y[t,:]    = x[t,:] . W_qkv                          every row (Algorithm 1, base output)
+ *   y[t,:]   += (x[t,:] . A[a]) . B[a],  a = adapter    rows with active(t) only
+ *   q_out[t,:]            = y[t, 0:Nq]
+ *   k_cache[slot[t], :]   = y[t, Nq:Nq+Nkv]             if slot_mapping[t] >= 0
+ *   v_cache[slot[t], :]   = y[t, Nq+Nkv:N]              if slot_mapping[t] >= 0
+ *
+ * with Nq = n_q_heads*head_dim, Nkv = n_kv_heads*head_dim, N = Nq + 2*Nkv.  The paper's
+ * mask (1 = position before the activation start, keep the base output) is the negation
+ * of active() for rows that have an adapter; rows are selected, not blended, so adapter
+ * data never reaches a pre-activation or base-model row.  Those rows come out bit-identical
+ * to a call in which every adapter id is -1, which is what lets base-model cache blocks be
+ * reused by aLoRA requests and vice versa (Sec. 2.3, Sec. 3).
+ *
+ * Conventions
+ *   - All data pointers are DEVICE pointers unless marked (host).  The caller owns every
+ *     buffer; the library allocates nothing and keeps no state between calls.
+ *   - All matrices are dense row-major.  dtype applies to x, W_qkv, A[i], B[i], q_out and
+ *     both caches alike.  Accumulation is fp32; the fp32 sum base+delta is rounded once
+ *     (nearest-even) to the storage type.
+ *   - The paged caches are [num_blocks, block_size, n_kv_heads, head_dim] = [n_slots, Nkv];
+ *     slot s is offset s % block_size of physical block s / block_size (Sec. 2.4).
+ *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream); calls return
+ *     without synchronising.  Calls that share a workspace must be stream-ordered.
+ *   - Return value: ALORA_OK or a negative status.  On any error nothing has been enqueued
+ *     and no device memory has been written.
+ *
+ * Shape limits (ALORA_ESHAPE otherwise)
+ *   bf16: hidden % 64 == 0; Nq % 8 == 0; Nkv % 8 == 0; rank in {8,16,24,...,64};
+ *   f32 : hidden % 4 == 0;  Nq % 4 == 0; Nkv % 4 == 0; 1 <= rank <= 64;
+ *   both: 0 <= n_adapters <= ALORA_MAX_ADAPTERS; n_slots % block_size == 0; T >= 0 (T == 0
+ *   is a successful no-op).  Adapters of lower rank are zero-padded by the caller; any
+ *   LoRA scaling factor is folded into B by the caller.
+ *
+ * Preconditions on device data (not checked on the fast path; alora_qkv_validate checks them)
+ *   -1 <= token_adapter_ids[t] < n_adapters; 0 <= token_seg_ids[t] < n_segments for rows that
+ *   have an adapter (segment and position of base-model rows are never read);
+ *   slot_mapping[t] == -1 or in [0, n_slots), the non-negative ones pairwise distinct;
+ *   factors of adapters that some active row uses hold finite values.
+ */
+#ifndef ALORA_QKV_H
+#define ALORA_QKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ALORA_F32 0
+#define ALORA_BF16 1
+
+#define ALORA_MAX_ADAPTERS 128
+#define ALORA_MAX_RANK 64
+
+#define ALORA_OK 0
+#define ALORA_EINVAL (-1)      /* null pointer, negative size, unknown dtype              */
+#define ALORA_ESHAPE (-2)      /* a shape limit above is violated                         */
+#define ALORA_EWORKSPACE (-3)  /* workspace null, misaligned (256 B) or too small          */
+#define ALORA_EHIP (-4)        /* a HIP call failed; see alora_last_hip_error()            */
+#define ALORA_EDATA (-5)       /* alora_qkv_validate found a violated data precondition    */
+
+/* Sizes of one call plus the two per-token index arrays of App. B. */
+typedef struct alora_dims {
+    int32_t dtype;                  /* ALORA_F32 or ALORA_BF16                                   */
+    int32_t T;                      /* scheduled tokens in the flattened batch                   */
+    int32_t hidden;
+    int32_t n_q_heads, n_kv_heads, head_dim;
+    int32_t n_adapters, rank;
+    int32_t n_segments;             /* G: number of requests / activation segments               */
+    int64_t n_slots;                /* slots in k_cache and in v_cache                           */
+    const int32_t *token_seg_ids;   /* [T] App. B req_indices                        (device)    */
+    const int32_t *token_positions; /* [T] App. B position_within_req, absolute      (device)    */
+} alora_dims;
+
+/* Where the integer results of the classification / grouping step sit inside the workspace
+ * after alora_qkv_classify_group or alora_qkv_forward (byte offsets from its start). */
+typedef struct alora_ws_layout {
+    size_t active_off;      /* uint8  [T]    1 = row receives its adapter's delta              */
+    size_t perm_off;        /* int32  [T]    first offsets[L] entries: active rows grouped by
+                                             adapter, increasing t inside a group (stable)     */
+    size_t offsets_off;     /* int32  [L+1]  group a is perm[offsets[a] .. offsets[a+1])        */
+    size_t total_bytes;     /* same value alora_qkv_workspace_bytes reports                    */
+} alora_ws_layout;
+
+/* Bytes of workspace alora_qkv_forward needs for these sizes.  Host only, touches no device. */
+int alora_qkv_workspace_bytes(const alora_dims *dims, size_t *out_bytes);
+
+/* Layout of the integer results inside the workspace.  Host only. */
+int alora_qkv_workspace_layout(const alora_dims *dims, alora_ws_layout *out);
+
+/*
+ * Row classification and grouping only (App. B mask; grouping of adapted rows by adapter id
+ * for the multi-adapter shrink): fills the workspace regions named by alora_ws_layout.
+ *   token_adapter_ids [T] device, -1 = base-model row;  activation_start [G] device.
+ */
+int alora_qkv_classify_group(const int32_t *token_adapter_ids, const int32_t *activation_start,
+                             const alora_dims *dims, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/*
+ * The whole path: classification, grouping, LoRA shrink on active rows, base projection with
+ * the low-rank expand added to active rows, q_out store and paged K/V store.
+ *
+ *   x                 [T, hidden]                              read
+ *   token_adapter_ids [T]  int32, -1 = base-model row          read
+ *   activation_start  [G]  int32, App. B inv_start             read
+ *   W_qkv             [hidden, N]  (y = x . W)                 read
+ *   A, B              (host) arrays of n_adapters device pointers, A[i] [hidden, rank],
+ *                     B[i] [rank, N]; the arrays are read before the call returns.  Factors
+ *                     of adapters that no active row uses are never dereferenced.
+ *   q_out             [T, Nq]            every row written
+ *   k_cache, v_cache  [n_slots, Nkv]     only the slots named by slot_mapping are written
+ *   slot_mapping      [T]  int64, -1 = no K/V write for this row (q_out is still produced)
+ *   block_size        tokens per cache block (> 0, divides n_slots)
+ *   workspace         device, 256-byte aligned, >= alora_qkv_workspace_bytes() bytes; contents
+ *                     on entry are irrelevant
+ */
+int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                      const void *W_qkv, const void *const *A, const void *const *B,
+                      void *q_out, void *k_cache, void *v_cache,
+                      const int64_t *slot_mapping, int32_t block_size,
+                      const alora_dims *dims, void *workspace, size_t workspace_bytes,
+                      void *hip_stream);
+
+/*
+ * Slow, synchronous check of the data preconditions listed at the top (copies the index
+ * arrays to the host).  Returns ALORA_OK, ALORA_EDATA, or another status for bad arguments.
+ * Writes no device memory.
+ */
+int alora_qkv_validate(const int32_t *token_adapter_ids, const int32_t *activation_start,
+                       const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims);
+
+/*
+ * Benchmark aid (not for serving loops: it creates HIP events).  Between _begin and _end, every
+ * alora_qkv_forward records a HIP event pair on its stream around its dominant kernel, the
+ * projection GEMM (Algorithm 1's base output with the adapter term fused in), for at most
+ * max_calls calls.  _end waits for the recorded events and reports the average duration of
+ * that kernel in milliseconds and how many calls were measured.
+ */
+int alora_qkv_profile_begin(int max_calls);
+int alora_qkv_profile_end(double *avg_ms, int *n_calls);
+
+/* Static description of a status code. */
+const char *alora_status_string(int status);
+
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int alora_last_hip_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int alora_qkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALORA_QKV_H */

@@ -1,0 +1,178 @@
+"""Thin Python binding over libalora_qkv.so (C ABI declared in include/alora_qkv.h).
+
+Argument marshalling only: torch tensors supply device memory and the stream; every step of
+the path runs in the library's HIP kernels.  There is no fallback: if the library is missing
+the import of any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libalora_qkv.so")
+
+ALORA_F32, ALORA_BF16 = 0, 1
+ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_EWORKSPACE, ALORA_EHIP, ALORA_EDATA = 0, -1, -2, -3, -4, -5
+ALORA_MAX_ADAPTERS, ALORA_MAX_RANK = 128, 64
+
+
+class AloraDims(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("T", ctypes.c_int32), ("hidden", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_adapters", ctypes.c_int32), ("rank", ctypes.c_int32), ("n_segments", ctypes.c_int32),
+                ("n_slots", ctypes.c_int64), ("token_seg_ids", ctypes.c_void_p),
+                ("token_positions", ctypes.c_void_p)]
+
+
+class AloraWsLayout(ctypes.Structure):
+    _fields_ = [("active_off", ctypes.c_size_t), ("perm_off", ctypes.c_size_t),
+                ("offsets_off", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t)]
+
+
+class AloraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().alora_status_string(status).decode()
+        if status == ALORA_EHIP:
+            msg += f" [hipError {lib().alora_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_17910_amd.build` "
+                              "(there is no non-HIP fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.alora_qkv_workspace_bytes.argtypes = [ctypes.POINTER(AloraDims), ctypes.POINTER(sz)]
+        L.alora_qkv_workspace_layout.argtypes = [ctypes.POINTER(AloraDims), ctypes.POINTER(AloraWsLayout)]
+        L.alora_qkv_classify_group.argtypes = [vp, vp, ctypes.POINTER(AloraDims), vp, sz, vp]
+        L.alora_qkv_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                        ctypes.POINTER(AloraDims), vp, sz, vp]
+        L.alora_qkv_validate.argtypes = [vp, vp, vp, i32, ctypes.POINTER(AloraDims)]
+        L.alora_status_string.argtypes = [ctypes.c_int]
+        L.alora_status_string.restype = ctypes.c_char_p
+        L.alora_qkv_profile_begin.argtypes = [ctypes.c_int]
+        L.alora_qkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+        for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
+                     "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return ALORA_BF16
+    if t.dtype == torch.float32:
+        return ALORA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def make_dims(dtype: int, T: int, hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+              n_adapters: int, rank: int, n_segments: int, n_slots: int,
+              token_seg_ids=None, token_positions=None) -> AloraDims:
+    return AloraDims(dtype, T, hidden, n_q_heads, n_kv_heads, head_dim, n_adapters, rank, n_segments,
+                     n_slots, _ptr(token_seg_ids), _ptr(token_positions))
+
+
+def alora_qkv_workspace_bytes(dims: AloraDims) -> int:
+    out = ctypes.c_size_t(0)
+    s = lib().alora_qkv_workspace_bytes(ctypes.byref(dims), ctypes.byref(out))
+    if s:
+        raise AloraError(s, "alora_qkv_workspace_bytes")
+    return int(out.value)
+
+
+def alora_qkv_workspace_layout(dims: AloraDims) -> AloraWsLayout:
+    out = AloraWsLayout()
+    s = lib().alora_qkv_workspace_layout(ctypes.byref(dims), ctypes.byref(out))
+    if s:
+        raise AloraError(s, "alora_qkv_workspace_layout")
+    return out
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def alloc_workspace(dims: AloraDims, device="cuda"):
+    import torch
+    return torch.empty(alora_qkv_workspace_bytes(dims), dtype=torch.uint8, device=device)
+
+
+def _ptr_array(tensors: Sequence):
+    arr = (ctypes.c_void_p * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def alora_qkv_classify_group(token_adapter_ids, activation_start, dims: AloraDims, workspace, stream=None):
+    """Runs the classification/grouping step; returns (active, perm, offsets) views of the workspace.
+    perm's first offsets[-1] entries are meaningful."""
+    import torch
+    s = lib().alora_qkv_classify_group(_ptr(token_adapter_ids), _ptr(activation_start), ctypes.byref(dims),
+                                       _ptr(workspace), workspace.numel(), _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_qkv_classify_group")
+    return workspace_int_views(dims, workspace)
+
+
+def workspace_int_views(dims: AloraDims, workspace):
+    import torch
+    lay = alora_qkv_workspace_layout(dims)
+    T, L = dims.T, dims.n_adapters
+    active = workspace[lay.active_off: lay.active_off + T]
+    perm = workspace[lay.perm_off: lay.perm_off + 4 * T].view(torch.int32)
+    offsets = workspace[lay.offsets_off: lay.offsets_off + 4 * (L + 1)].view(torch.int32)
+    return active, perm, offsets
+
+
+def alora_qkv_forward(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
+                      q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims,
+                      workspace, stream=None) -> None:
+    """Enqueue the whole path on `stream` (default: torch's current stream).  Returns nothing;
+    q_out and the mapped cache slots are written asynchronously."""
+    s = lib().alora_qkv_forward(_ptr(x), _ptr(token_adapter_ids), _ptr(activation_start), _ptr(W_qkv),
+                                _ptr_array(A), _ptr_array(B), _ptr(q_out), _ptr(k_cache), _ptr(v_cache),
+                                _ptr(slot_mapping), block_size, ctypes.byref(dims), _ptr(workspace),
+                                workspace.numel() if workspace is not None else 0, _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_qkv_forward")
+
+
+def alora_qkv_validate(token_adapter_ids, activation_start, slot_mapping, block_size: int, dims: AloraDims) -> int:
+    return int(lib().alora_qkv_validate(_ptr(token_adapter_ids), _ptr(activation_start), _ptr(slot_mapping),
+                                        block_size, ctypes.byref(dims)))
+
+
+def alora_qkv_profile_begin(max_calls: int) -> None:
+    s = lib().alora_qkv_profile_begin(max_calls)
+    if s:
+        raise AloraError(s, "alora_qkv_profile_begin")
+
+
+def alora_qkv_profile_end():
+    """(average milliseconds of the dominant kernel, number of measured calls)."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    s = lib().alora_qkv_profile_end(ctypes.byref(ms), ctypes.byref(n))
+    if s:
+        raise AloraError(s, "alora_qkv_profile_end")
+    return float(ms.value), int(n.value)

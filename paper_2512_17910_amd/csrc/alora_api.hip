@@ -1,0 +1,283 @@
+// C ABI of libalora_qkv: argument checking, workspace carving and the launch sequence.
+// Host code only; every step of the path runs in the kernels of the other translation units.
+#include <vector>
+#include <algorithm>
+#include "alora_internal.h"
+
+namespace alora {
+
+static thread_local int g_last_hip_error = 0;
+
+// Benchmark aid: HIP events around the dominant kernel (the projection GEMM) of each forward call.
+struct Profile {
+    bool on = false;
+    int used = 0;
+    std::vector<hipEvent_t> ev0, ev1;
+};
+static Profile g_prof;
+
+static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout {
+    size_t active, perm, offsets, S, partial, total;
+};
+
+static int check_dims(const alora_dims *d)
+{
+    if (!d) return ALORA_EINVAL;
+    if (d->dtype != ALORA_F32 && d->dtype != ALORA_BF16) return ALORA_EINVAL;
+    if (d->T < 0 || d->hidden <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 ||
+        d->n_adapters < 0 || d->n_segments < 0 || d->n_slots < 0 || d->rank < 0)
+        return ALORA_EINVAL;
+    const long long Nq = (long long)d->n_q_heads * d->head_dim, Nkv = (long long)d->n_kv_heads * d->head_dim;
+    if (Nq + 2 * Nkv > (1ll << 30) || (long long)d->T * d->hidden > (1ll << 40)) return ALORA_ESHAPE;
+    if (d->n_adapters > ALORA_MAX_ADAPTERS) return ALORA_ESHAPE;
+    if (d->n_adapters > 0 && (d->rank < 1 || d->rank > ALORA_MAX_RANK)) return ALORA_ESHAPE;
+    if (d->dtype == ALORA_BF16) {
+        if (d->hidden % 64 || Nq % 8 || Nkv % 8) return ALORA_ESHAPE;
+        if (d->n_adapters > 0 && d->rank % 8) return ALORA_ESHAPE;
+    } else {
+        if (d->hidden % 4 || Nq % 4 || Nkv % 4) return ALORA_ESHAPE;
+    }
+    return ALORA_OK;
+}
+
+static Layout make_layout(const alora_dims *d)
+{
+    Layout l;
+    const size_t T = (size_t)d->T, L = (size_t)d->n_adapters, r = (size_t)d->rank;
+    size_t o = 0;
+    l.active = o;  o += up256(T);
+    l.perm = o;    o += up256(4 * T);
+    l.offsets = o; o += up256(4 * (L + 1));
+    l.S = o;       o += up256(T * r * 4);  // f32: [T,r] fp32; bf16: [T,2r] bf16
+    l.partial = o;
+    if (d->dtype == ALORA_BF16)
+        o += up256(bf16_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
+    l.total = std::max<size_t>(o, 256);
+    return l;
+}
+
+static int check_ws(const alora_dims *d, const void *ws, size_t bytes, Layout *l)
+{
+    *l = make_layout(d);
+    if (!ws || ((uintptr_t)ws & 255) || bytes < l->total) return ALORA_EWORKSPACE;
+    return ALORA_OK;
+}
+
+static bool misaligned16(const void *p) { return ((uintptr_t)p & 15) != 0; }
+
+static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, void *stream)
+{
+    f.dtype = d->dtype; f.T = d->T; f.H = d->hidden;
+    f.Nq = d->n_q_heads * d->head_dim; f.Nkv = d->n_kv_heads * d->head_dim; f.N = f.Nq + 2 * f.Nkv;
+    f.L = d->n_adapters; f.r = d->rank; f.G = d->n_segments; f.n_slots = d->n_slots;
+    f.seg = d->token_seg_ids; f.pos = d->token_positions;
+    unsigned char *b = (unsigned char *)ws;
+    f.active = b + l.active;
+    f.perm = (int32_t *)(b + l.perm);
+    f.offsets = (int32_t *)(b + l.offsets);
+    f.S = b + l.S;
+    f.partial = (float *)(b + l.partial);
+    f.stream = (hipStream_t)stream;
+}
+
+}  // namespace alora
+
+using namespace alora;
+
+extern "C" {
+
+int alora_qkv_version(void) { return 100; }
+
+int alora_last_hip_error(void) { return g_last_hip_error; }
+
+const char *alora_status_string(int s)
+{
+    switch (s) {
+    case ALORA_OK: return "ok";
+    case ALORA_EINVAL: return "invalid argument (null or misaligned pointer, negative size, unknown dtype)";
+    case ALORA_ESHAPE: return "unsupported shape (see the shape limits in alora_qkv.h)";
+    case ALORA_EWORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
+    case ALORA_EHIP: return "a HIP call failed (see alora_last_hip_error)";
+    case ALORA_EDATA: return "device data violates a documented precondition";
+    default: return "unknown status";
+    }
+}
+
+int alora_qkv_workspace_bytes(const alora_dims *dims, size_t *out_bytes)
+{
+    if (!out_bytes) return ALORA_EINVAL;
+    int s = check_dims(dims);
+    if (s) return s;
+    *out_bytes = make_layout(dims).total;
+    return ALORA_OK;
+}
+
+int alora_qkv_workspace_layout(const alora_dims *dims, alora_ws_layout *out)
+{
+    if (!out) return ALORA_EINVAL;
+    int s = check_dims(dims);
+    if (s) return s;
+    const Layout l = make_layout(dims);
+    out->active_off = l.active;
+    out->perm_off = l.perm;
+    out->offsets_off = l.offsets;
+    out->total_bytes = l.total;
+    return ALORA_OK;
+}
+
+int alora_qkv_classify_group(const int32_t *token_adapter_ids, const int32_t *activation_start,
+                             const alora_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int s = check_dims(dims);
+    if (s) return s;
+    if (dims->T > 0 && (!token_adapter_ids || !dims->token_seg_ids || !dims->token_positions)) return ALORA_EINVAL;
+    if (dims->T > 0 && dims->n_segments > 0 && !activation_start) return ALORA_EINVAL;
+    Layout l;
+    s = check_ws(dims, workspace, workspace_bytes, &l);
+    if (s) return s;
+    Fwd f = {};
+    fill_common(f, dims, l, workspace, hip_stream);
+    f.aid = token_adapter_ids; f.start = activation_start;
+    int e = launch_classify_group(f);
+    if (e) { g_last_hip_error = e; return ALORA_EHIP; }
+    return ALORA_OK;
+}
+
+int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                      const void *W_qkv, const void *const *A, const void *const *B, void *q_out, void *k_cache,
+                      void *v_cache, const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int s = check_dims(dims);
+    if (s) return s;
+    if (block_size <= 0) return ALORA_EINVAL;
+    if (dims->n_slots % block_size) return ALORA_ESHAPE;
+    if (dims->T > 0) {
+        if (!x || !token_adapter_ids || !W_qkv || !q_out || !slot_mapping || !dims->token_seg_ids ||
+            !dims->token_positions)
+            return ALORA_EINVAL;
+        if (dims->n_slots > 0 && (!k_cache || !v_cache)) return ALORA_EINVAL;
+        if (dims->n_segments > 0 && !activation_start) return ALORA_EINVAL;
+        if (misaligned16(x) || misaligned16(W_qkv) || misaligned16(q_out) || misaligned16(k_cache) ||
+            misaligned16(v_cache))
+            return ALORA_EINVAL;
+    }
+    PtrTable ta = {}, tb = {};
+    if (dims->n_adapters > 0) {
+        if (!A || !B) return ALORA_EINVAL;
+        for (int i = 0; i < dims->n_adapters; ++i) {
+            if (!A[i] || !B[i] || misaligned16(A[i]) || misaligned16(B[i])) return ALORA_EINVAL;
+            ta.p[i] = A[i];
+            tb.p[i] = B[i];
+        }
+    }
+    Layout l;
+    s = check_ws(dims, workspace, workspace_bytes, &l);
+    if (s) return s;
+    if (dims->T == 0) return ALORA_OK;
+
+    Fwd f = {};
+    fill_common(f, dims, l, workspace, hip_stream);
+    f.block_size = block_size;
+    f.x = x; f.W = W_qkv; f.aid = token_adapter_ids; f.start = activation_start; f.slot = slot_mapping;
+    f.q = q_out; f.kc = k_cache; f.vc = v_cache;
+
+    const bool timed = g_prof.on && g_prof.used < (int)g_prof.ev0.size();
+    int e = launch_classify_group(f);
+    if (!e) {
+        if (f.dtype == ALORA_F32) {
+            e = launch_shrink_f32(f, ta);
+            if (!e && timed) e = (int)hipEventRecord(g_prof.ev0[g_prof.used], f.stream);
+            if (!e) e = launch_gemm_f32(f, tb);
+        } else {
+            e = launch_shrink_bf16(f, ta);
+            if (!e && timed) e = (int)hipEventRecord(g_prof.ev0[g_prof.used], f.stream);
+            if (!e) e = launch_gemm_bf16(f, tb);
+        }
+        if (!e && timed) {
+            e = (int)hipEventRecord(g_prof.ev1[g_prof.used], f.stream);
+            g_prof.used++;
+        }
+    }
+    if (e) { g_last_hip_error = e; return ALORA_EHIP; }
+    return ALORA_OK;
+}
+
+int alora_qkv_profile_begin(int max_calls)
+{
+    if (max_calls <= 0 || max_calls > (1 << 20)) return ALORA_EINVAL;
+    if (g_prof.on) return ALORA_EINVAL;
+    g_prof.ev0.assign((size_t)max_calls, nullptr);
+    g_prof.ev1.assign((size_t)max_calls, nullptr);
+    for (int i = 0; i < max_calls; ++i) {
+        hipError_t e = hipEventCreate(&g_prof.ev0[i]);
+        if (!e) e = hipEventCreate(&g_prof.ev1[i]);
+        if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+    }
+    g_prof.used = 0;
+    g_prof.on = true;
+    return ALORA_OK;
+}
+
+int alora_qkv_profile_end(double *avg_ms, int *n_calls)
+{
+    if (!g_prof.on) return ALORA_EINVAL;
+    g_prof.on = false;
+    double sum = 0.0;
+    int n = 0, status = ALORA_OK;
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(g_prof.ev1[i]);
+        if (!e) e = hipEventElapsedTime(&ms, g_prof.ev0[i], g_prof.ev1[i]);
+        if (e) { g_last_hip_error = (int)e; status = ALORA_EHIP; break; }
+        sum += ms;
+        ++n;
+    }
+    for (size_t i = 0; i < g_prof.ev0.size(); ++i) {
+        if (g_prof.ev0[i]) (void)hipEventDestroy(g_prof.ev0[i]);
+        if (g_prof.ev1[i]) (void)hipEventDestroy(g_prof.ev1[i]);
+    }
+    g_prof.ev0.clear();
+    g_prof.ev1.clear();
+    if (avg_ms) *avg_ms = n ? sum / n : 0.0;
+    if (n_calls) *n_calls = n;
+    return status;
+}
+
+int alora_qkv_validate(const int32_t *token_adapter_ids, const int32_t *activation_start,
+                       const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims)
+{
+    int s = check_dims(dims);
+    if (s) return s;
+    if (block_size <= 0) return ALORA_EINVAL;
+    if (dims->n_slots % block_size) return ALORA_ESHAPE;
+    const size_t T = (size_t)dims->T;
+    if (T == 0) return ALORA_OK;
+    if (!token_adapter_ids || !slot_mapping || !dims->token_seg_ids || !dims->token_positions) return ALORA_EINVAL;
+    if (dims->n_segments > 0 && !activation_start) return ALORA_EINVAL;
+    std::vector<int32_t> aid(T), seg(T), pos(T), start((size_t)dims->n_segments);
+    std::vector<int64_t> slot(T);
+    hipError_t e = hipMemcpy(aid.data(), token_adapter_ids, 4 * T, hipMemcpyDeviceToHost);
+    if (!e) e = hipMemcpy(seg.data(), dims->token_seg_ids, 4 * T, hipMemcpyDeviceToHost);
+    if (!e) e = hipMemcpy(pos.data(), dims->token_positions, 4 * T, hipMemcpyDeviceToHost);
+    if (!e) e = hipMemcpy(slot.data(), slot_mapping, 8 * T, hipMemcpyDeviceToHost);
+    if (!e && dims->n_segments > 0)
+        e = hipMemcpy(start.data(), activation_start, 4 * (size_t)dims->n_segments, hipMemcpyDeviceToHost);
+    if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+    for (size_t t = 0; t < T; ++t) {
+        if (aid[t] < -1 || aid[t] >= dims->n_adapters) return ALORA_EDATA;
+        if (aid[t] >= 0 && (seg[t] < 0 || seg[t] >= dims->n_segments)) return ALORA_EDATA;
+        if (slot[t] < -1 || slot[t] >= dims->n_slots) return ALORA_EDATA;
+    }
+    std::vector<int64_t> used;
+    used.reserve(T);
+    for (size_t t = 0; t < T; ++t)
+        if (slot[t] >= 0) used.push_back(slot[t]);
+    std::sort(used.begin(), used.end());
+    if (std::adjacent_find(used.begin(), used.end()) != used.end()) return ALORA_EDATA;
+    return ALORA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Internal declarations shared by the HIP translation units of libalora_qkv (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "alora_qkv.h"
+
+namespace alora {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Device pointers of the adapters' factors, passed to kernels by value.
+struct PtrTable {
+    const void *p[ALORA_MAX_ADAPTERS];
+};
+
+// Everything one forward call needs, resolved on the host.
+struct Fwd {
+    int dtype, T, H, Nq, Nkv, N, L, r, G;
+    long long n_slots;
+    int block_size;
+    const void *x, *W;
+    const int32_t *aid, *seg, *pos, *start;
+    const int64_t *slot;
+    void *q, *kc, *vc;
+    // workspace regions
+    uint8_t *active;
+    int32_t *perm, *offsets;
+    void *S;          // bf16: [T,2r] bf16 (hi | lo halves of the fp32 shrink result); f32: [T,r] fp32
+    float *partial;   // split-K partial sums of the decode-shaped path (bf16 only)
+    hipStream_t stream;
+};
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// App. B mask negated and combined with "row has an adapter": -1 when the row keeps the base
+// output, else its adapter id.  seg/pos/start are only read for rows that have an adapter.
+__device__ __forceinline__ int effective_adapter(const int32_t *aid, const int32_t *seg, const int32_t *pos,
+                                                 const int32_t *start, int t)
+{
+    int a = aid[t];
+    if (a < 0) return -1;
+    return (pos[t] >= start[seg[t]]) ? a : -1;
+}
+
+// launches (each returns the hipError_t of its launch as int)
+int launch_classify_group(const Fwd &f);
+int launch_shrink_f32(const Fwd &f, const PtrTable &A);
+int launch_gemm_f32(const Fwd &f, const PtrTable &B);
+int launch_shrink_bf16(const Fwd &f, const PtrTable &A);
+int launch_gemm_bf16(const Fwd &f, const PtrTable &B);
+size_t bf16_partial_bytes(int T, int H, int N);
+
+}  // namespace alora

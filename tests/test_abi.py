@@ -1,0 +1,106 @@
+"""The C-ABI library loads, exports every symbol include/alora_qkv.h declares, and its host-side
+argument checks answer without touching a GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_17910_amd import binding as ab
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "alora_qkv.h")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(alora_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"alora_qkv_forward", "alora_qkv_workspace_bytes", "alora_qkv_classify_group",
+            "alora_qkv_validate", "alora_status_string"} <= set(names)
+    L = ab.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in the header but not exported"
+
+
+def test_header_constants_match_binding():
+    src = open(HEADER).read()
+    for name in ("ALORA_F32", "ALORA_BF16", "ALORA_MAX_ADAPTERS", "ALORA_MAX_RANK", "ALORA_OK"):
+        m = re.search(rf"#define {name} \(?(-?\d+)\)?", src)
+        assert m and int(m.group(1)) == getattr(ab, name)
+    for name in ("ALORA_EINVAL", "ALORA_ESHAPE", "ALORA_EWORKSPACE", "ALORA_EHIP", "ALORA_EDATA"):
+        m = re.search(rf"#define {name} \((-?\d+)\)", src)
+        assert m and int(m.group(1)) == getattr(ab, name)
+
+
+def _dims(**kw):
+    d = dict(dtype=ab.ALORA_BF16, T=128, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, n_adapters=2,
+             rank=16, n_segments=2, n_slots=256)
+    d.update(kw)
+    dims = ab.make_dims(**d)
+    dims.token_seg_ids = 0x10000
+    dims.token_positions = 0x20000
+    return dims
+
+
+def test_workspace_size_and_layout():
+    d = _dims()
+    n = ab.alora_qkv_workspace_bytes(d)
+    lay = ab.alora_qkv_workspace_layout(d)
+    assert n == lay.total_bytes and n % 256 == 0
+    assert lay.active_off % 256 == 0 and lay.perm_off >= lay.active_off + d.T
+    assert lay.offsets_off >= lay.perm_off + 4 * d.T
+    assert ab.alora_qkv_workspace_bytes(_dims(T=0)) >= 256
+    assert ab.alora_qkv_workspace_bytes(_dims(T=4096)) > n
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(dtype=7), ab.ALORA_EINVAL),
+    (dict(T=-1), ab.ALORA_EINVAL),
+    (dict(hidden=100), ab.ALORA_ESHAPE),            # bf16 needs hidden % 64 == 0
+    (dict(head_dim=3), ab.ALORA_ESHAPE),            # Nq % 8
+    (dict(rank=12), ab.ALORA_ESHAPE),               # bf16 rank % 8
+    (dict(rank=72), ab.ALORA_ESHAPE),
+    (dict(n_adapters=129), ab.ALORA_ESHAPE),
+    (dict(dtype=ab.ALORA_F32, hidden=6), ab.ALORA_ESHAPE),
+])
+def test_bad_dims_are_rejected(kw, status):
+    out = ctypes.c_size_t(0)
+    d = _dims(**kw)
+    assert ab.lib().alora_qkv_workspace_bytes(ctypes.byref(d), ctypes.byref(out)) == status
+
+
+def test_forward_rejects_bad_arguments_before_any_launch():
+    """Fake (never dereferenced) pointers: every call must fail in the host-side checks."""
+    L = ab.lib()
+    d = _dims()
+    need = ab.alora_qkv_workspace_bytes(d)
+    P = 0x100000  # 16-byte and 256-byte aligned dummy address
+    tab = (ctypes.c_void_p * 2)(P, P)
+
+    def call(x=P, aid=P, start=P, W=P, A=tab, B=tab, q=P, kc=P, vc=P, slot=P, bs=16, dims=d, ws=P, wsb=need):
+        return L.alora_qkv_forward(x, aid, start, W, A, B, q, kc, vc, slot, bs, ctypes.byref(dims), ws, wsb, None)
+
+    assert call(x=None) == ab.ALORA_EINVAL
+    assert call(W=None) == ab.ALORA_EINVAL
+    assert call(q=None) == ab.ALORA_EINVAL
+    assert call(slot=None) == ab.ALORA_EINVAL
+    assert call(kc=None) == ab.ALORA_EINVAL
+    assert call(A=None) == ab.ALORA_EINVAL
+    assert call(x=P + 2) == ab.ALORA_EINVAL
+    assert call(bs=0) == ab.ALORA_EINVAL
+    assert call(bs=24) == ab.ALORA_ESHAPE            # 256 slots not a multiple of 24
+    assert call(ws=None) == ab.ALORA_EWORKSPACE
+    assert call(ws=P + 16) == ab.ALORA_EWORKSPACE
+    assert call(wsb=need - 1) == ab.ALORA_EWORKSPACE
+    tab_bad = (ctypes.c_void_p * 2)(P, None)
+    assert call(B=tab_bad) == ab.ALORA_EINVAL
+    assert call(dims=_dims(rank=12)) == ab.ALORA_ESHAPE
+    # T == 0 is a successful no-op that needs no data pointers
+    assert call(x=None, aid=None, W=None, q=None, slot=None, dims=_dims(T=0)) == ab.ALORA_OK
+    assert L.alora_status_string(ab.ALORA_ESHAPE).decode().startswith("unsupported shape")
+    assert L.alora_qkv_version() >= 100

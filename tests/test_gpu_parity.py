@@ -1,0 +1,199 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same
+seeded inputs.  Integer/index results bit-exact; floating point within the stated max-norm
+relative error (1e-5 fp32, 2e-2 bf16); pre-activation rows bit-identical to a base-only GPU run."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_17910_amd import binding as ab
+from paper_2512_17910_amd import workloads as wl
+from gpu_util import DeviceBatch, TOL, host_operands, maxnorm_rel, raw_bits, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_full(w):
+    x, W, A, B = host_operands(w)
+    k0 = wl.widen_f64(wl.cache_fill(w.n_slots, w.Nkv, w.dtype, 0), w.dtype)
+    v0 = wl.widen_f64(wl.cache_fill(w.n_slots, w.Nkv, w.dtype, 1), w.dtype)
+    return oracle.alora_qkv_forward(x, w.token_adapter_ids, w.token_seg_ids, w.token_positions,
+                                    w.activation_start, W, A, B, w.slot_mapping, w.block_size, w.Nq, w.Nkv, k0, v0)
+
+
+def _check_full(w, db=None, elementwise=True):
+    """Every element of q_out and of both caches against the oracle."""
+    print(f"[case] {w.name} T={w.T} H={w.hidden} N={w.N} L={w.n_adapters} r={w.rank}", flush=True)
+    db = db or DeviceBatch(w)
+    assert db.validate() == ab.ALORA_OK
+    db.forward()
+    ref = _oracle_full(w)
+    tol = TOL[w.dtype]
+    q, kc, vc = to_f64(db.q), to_f64(db.kc), to_f64(db.vc)
+    wr = ref.written_slots
+    assert maxnorm_rel(q, ref.q_out) <= tol
+    assert maxnorm_rel(kc[wr], ref.k_cache[wr]) <= tol
+    assert maxnorm_rel(vc[wr], ref.v_cache[wr]) <= tol
+    if elementwise:
+        # tighter, per element: one rounding to storage precision plus fp32 accumulation noise
+        u, floor = (2.0 ** -8, 2.0 ** -12) if w.dtype == "bf16" else (2.0 ** -20, 4e-6)
+        scale = np.max(np.abs(ref.q_out)) if ref.q_out.size else 1.0
+        for got, want in ((q, ref.q_out), (kc[wr], ref.k_cache[wr]), (vc[wr], ref.v_cache[wr])):
+            assert np.all(np.abs(got - want) <= u * np.abs(want) + floor * scale)
+    # slots that no token names keep their bytes
+    un = np.setdiff1d(np.arange(w.n_slots), wr)
+    assert np.array_equal(raw_bits(db.kc)[un], raw_bits(db.k0)[un])
+    assert np.array_equal(raw_bits(db.vc)[un], raw_bits(db.v0)[un])
+    # integer results left in the workspace
+    act, perm, off = ab.workspace_int_views(db.dims, db.ws)
+    assert np.array_equal(act.cpu().numpy(), ref.active)
+    assert np.array_equal(off.cpu().numpy(), ref.offsets)
+    assert np.array_equal(perm.cpu().numpy()[: ref.perm.size], ref.perm)
+    return db, ref
+
+
+def test_config1_fp32():
+    db, ref = _check_full(wl.config1())
+    assert int(ref.active.sum()) == 8
+
+
+SMALL = [
+    dict(dtype="bf16", seed=1),
+    dict(dtype="bf16", seed=2, seq_lens=(300, 41, 1, 77, 256, 3), pad_every=17),
+    dict(dtype="bf16", seed=3, n_q_heads=5, n_kv_heads=2, head_dim=40, hidden=192, rank=8, seq_lens=(70, 9)),
+    dict(dtype="bf16", seed=4, rank=64, n_adapters=2, hidden=128, seq_lens=(33, 64, 31)),
+    dict(dtype="bf16", seed=5, rank=24, n_adapters=5, hidden=320, n_q_heads=9, head_dim=32, seq_lens=(513, 5)),
+    dict(dtype="f32", seed=6, hidden=100, n_q_heads=3, n_kv_heads=1, head_dim=20, rank=5, seq_lens=(70, 9, 130)),
+    dict(dtype="f32", seed=7, rank=64, pad_every=5),
+]
+
+
+@pytest.mark.parametrize("kw", SMALL, ids=[f"{k['dtype']}-{k['seed']}" for k in SMALL])
+def test_small_mixed(kw):
+    _check_full(wl.small_mixed(**kw))
+
+
+def test_decode_like_many_adapters():
+    """One token per sequence, many adapters inside one tile, some base-only rows."""
+    segs = []
+    rng = np.random.default_rng(9)
+    for s in range(200):
+        p = int(rng.integers(1, 100))
+        a = -1 if s % 5 == 0 else int(rng.integers(0, 16))
+        segs.append(wl.Segment(s, p, 1, a, int(rng.integers(0, p + 1))))
+    w = wl.assemble("decode-like", "bf16", 256, 4, 2, 64, 16, 32, 16, segs, [100] * 200, seed=99, extra_blocks=3)
+    _check_full(w)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_pre_activation_rows_bit_identical_to_base_run(dtype):
+    w = wl.small_mixed(dtype, seed=2, seq_lens=(300, 41, 1, 77, 256, 3))
+    db = DeviceBatch(w)
+    db.forward()
+    q1, k1, v1 = raw_bits(db.q), raw_bits(db.kc), raw_bits(db.vc)
+    db.reset()
+    base_ids = torch.full_like(db.aid, -1)
+    db.forward(aid=base_ids)
+    q0, k0, v0 = raw_bits(db.q), raw_bits(db.kc), raw_bits(db.vc)
+    _, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+    pre = act == 0
+    assert pre.any() and (~pre).any()
+    assert np.array_equal(q1[pre], q0[pre])
+    sl = w.slot_mapping
+    pre_slots = sl[pre & (sl >= 0)]
+    assert np.array_equal(k1[pre_slots], k0[pre_slots]) and np.array_equal(v1[pre_slots], v0[pre_slots])
+    act_rows = ~pre
+    assert not np.array_equal(q1[act_rows], q0[act_rows])
+    # run-to-run determinism of the adapted call
+    db.reset()
+    db.forward()
+    assert np.array_equal(raw_bits(db.q), q1) and np.array_equal(raw_bits(db.kc), k1)
+    assert np.array_equal(raw_bits(db.vc), v1)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_base_rows_never_see_adapter_data(dtype):
+    """All rows base-only while A and B hold NaN: the result is the base projection (select, not blend)."""
+    w = wl.small_mixed(dtype, seed=1)
+    db = DeviceBatch(w)
+    base_ids = torch.full_like(db.aid, -1)
+    db.forward(aid=base_ids)
+    q0 = raw_bits(db.q)
+    nanA = [torch.full_like(a, float("nan")) for a in db.A]
+    nanB = [torch.full_like(b, float("nan")) for b in db.B]
+    db.reset()
+    db.forward(aid=base_ids, A=nanA, B=nanB)
+    assert np.array_equal(raw_bits(db.q), q0)
+    x, W, _, _ = host_operands(w)
+    ref = oracle.base_rows(x, W, np.arange(w.T, dtype=np.int32))
+    assert maxnorm_rel(to_f64(db.q), ref[:, : w.Nq]) <= TOL[dtype]
+    # mixed batch, NaN only in an adapter no active row uses
+    db.reset()
+    used = set(int(a) for a in w.token_adapter_ids[w.token_adapter_ids >= 0])
+    unused = [i for i in range(w.n_adapters) if i not in used]
+    if unused:
+        A2 = list(db.A); B2 = list(db.B)
+        A2[unused[0]] = nanA[unused[0]]; B2[unused[0]] = nanB[unused[0]]
+        db.forward(A=A2, B=B2)
+        assert np.isfinite(to_f64(db.q)).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_degenerate_batches(dtype):
+    # no adapters at all
+    w = wl.small_mixed(dtype, seed=8, n_adapters=1, seq_lens=(5, 9))
+    w.token_adapter_ids[:] = -1
+    w.n_adapters = 0; w.A = []; w.B = []
+    _check_full(w)
+    # every row adapted from position 0 (standard LoRA)
+    segs = [wl.Segment(0, 0, 70, 1, 0), wl.Segment(1, 3, 9, 0, 0)]
+    _check_full(wl.assemble("all-active", dtype, 128, 2, 1, 64, 2, 16, 8, segs, [70, 12], seed=5))
+    # never activated, and no K/V written anywhere (all slots -1)
+    segs = [wl.Segment(0, 0, 40, 0, 40)]
+    w = wl.assemble("none-active", dtype, 128, 2, 1, 64, 1, 8, 16, segs, [40], seed=6, pad_rows=range(40))
+    w.token_adapter_ids[:] = 0
+    _check_full(w)
+    # a single token
+    _check_full(wl.assemble("one-token", dtype, 64, 1, 1, 32, 1, 8, 4, [wl.Segment(0, 6, 1, 0, 6)], [7], seed=7))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_empty_batch_is_a_noop(dtype):
+    w = wl.assemble("empty", dtype, 64, 1, 1, 32, 1, 8, 4, [], [], seed=3, extra_blocks=2)
+    db = DeviceBatch(w)
+    db.forward()
+    assert np.array_equal(raw_bits(db.kc), raw_bits(db.k0))
+
+
+def test_classify_group_large_random():
+    """Grouping alone on batches far larger than one tile, up to the adapter limit."""
+    rng = np.random.default_rng(4)
+    for T, L, G in ((1, 1, 1), (63, 2, 3), (5000, 128, 40), (26176, 32, 12)):
+        aid = rng.integers(-1, L, size=T).astype(np.int32)
+        seg = rng.integers(0, G, size=T).astype(np.int32)
+        pos = rng.integers(0, 50, size=T).astype(np.int32)
+        start = rng.integers(0, 50, size=G).astype(np.int32)
+        mask, act = oracle.classify(aid, seg, pos, start)
+        perm, off = oracle.group(aid, act, L)
+        d = [torch.from_numpy(a).to("cuda") for a in (aid, seg, pos, start)]
+        dims = ab.make_dims(ab.ALORA_BF16, T, 64, 1, 1, 8, L, 8, G, 16, d[1], d[2])
+        ws = ab.alloc_workspace(dims)
+        a_g, p_g, o_g = ab.alora_qkv_classify_group(d[0], d[3], dims, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(a_g.cpu().numpy(), act)
+        assert np.array_equal(o_g.cpu().numpy(), off)
+        assert np.array_equal(p_g.cpu().numpy()[: perm.size], perm)
+
+
+def test_validate_reports_bad_data():
+    w = wl.small_mixed("bf16", seed=1)
+    db = DeviceBatch(w)
+    assert db.validate() == ab.ALORA_OK
+    db.slot[1] = db.slot[0]
+    assert db.validate() == ab.ALORA_EDATA
+    db.slot[1] = w.n_slots
+    assert db.validate() == ab.ALORA_EDATA
+    db.slot[1] = -1
+    assert db.validate() == ab.ALORA_OK
+    db.aid[0] = w.n_adapters
+    assert db.validate() == ab.ALORA_EDATA
