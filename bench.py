@@ -1,0 +1,137 @@
+#!/usr/bin/env python3
+"""Benchmark of the masked multi-adapter aLoRA QKV projection + paged K/V write on one MI355X.
+
+A "step" is one alora_qkv_forward call (classification/grouping, LoRA shrink, fused projection with
+expand/select and the q_out + paged K/V stores) over one synthetic batch already resident in HBM.
+Prints ONE JSON line: whole-job tokens/s, the roofline figures of the dominant kernel (the fused
+projection GEMM, timed with HIP events recorded on the launch stream inside the timed region), and
+the CPU fp64 oracle timed on the host cores over a bounded sample of the same batch.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+METRIC = "masked-aLoRA QKV tokens/s at 1 MI355X; % bf16 MFMA peak / % HBM GB/s"
+BOUND = {2: "mfma", 3: "hbm", 4: "mfma", 5: "mfma"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5))
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="distinct copies of W/A/B cycled through (0 = 8 for the decode config, else 1)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2512_17910_amd import binding as ab
+    from paper_2512_17910_amd import workloads as wl
+    from gpu_util import DeviceBatch, host_operands, maxnorm_rel, to_dev, to_f64
+
+    ab.lib()  # fail loudly if the HIP library is missing
+    w = wl.CONFIGS[args.config]()
+    db = DeviceBatch(w, cache_fill=False)
+    rotate = args.rotate or (8 if args.config == 3 else 1)
+    copies = [(db.W, db.A, db.B)]
+    for _ in range(rotate - 1):
+        copies.append((db.W.clone(), [a.clone() for a in db.A], [b.clone() for b in db.B]))
+
+    def step(i):
+        W, A, B = copies[i % rotate]
+        ab.alora_qkv_forward(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot,
+                             w.block_size, db.dims, db.ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ab.alora_qkv_profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    gemm_ms, n_meas = ab.alora_qkv_profile_end()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.T * args.steps / (t1 - t0)
+
+    # algorithmic work of the dominant kernel (fused projection): base GEMM + expand on active rows
+    _, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+    T_act = int(act.sum())
+    used = len(set(int(a) for a in w.token_adapter_ids[act == 1]))
+    T_w = int((w.slot_mapping >= 0).sum())
+    e = w.elem_bytes
+    flops = 2.0 * w.T * w.hidden * w.N + 2.0 * T_act * w.rank * w.N
+    bytes_ = e * (w.T * w.hidden + w.hidden * w.N + used * w.rank * w.N + T_act * 2 * w.rank
+                  + w.T * w.Nq + T_w * 2 * w.Nkv) + w.T * (4 + 4 + 4 + 8) + 4 * w.n_segments
+    bound = BOUND[args.config]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(w.name, {}).get("hbm_bytes_per_launch")
+    if bound == "mfma":
+        achieved = flops / (gemm_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic}
+    else:
+        achieved = bytes_ / (gemm_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS, "traffic": traffic}
+    roof.update({"kernel": "alora_gemm_bf16_kernel", "kernel_ms": gemm_ms, "launches_timed": n_meas,
+                 "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": bytes_})
+
+    out = {"metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": w.name, "T": w.T, "hidden": w.hidden, "N": w.N, "n_adapters": w.n_adapters,
+                      "rank": w.rank, "active_rows": T_act, "block_size": w.block_size,
+                      "weight_copies_rotated": rotate},
+           "roofline": roof}
+
+    if not args.no_cpu_baseline:
+        x, W, A, B = host_operands(w)
+        threads = oracle.num_threads()
+        probe = wl.sample_rows(w, threads)          # about one row per thread
+        tp = time.perf_counter()
+        oracle.alora_rows(x, W, A, B, w.token_adapter_ids, act, probe)
+        row_time = (time.perf_counter() - tp) / max(1, -(-len(probe) // threads))
+        n = int(max(threads, min(w.T, args.cpu_seconds * threads / max(row_time, 1e-9))))
+        rows = wl.sample_rows(w, n)
+        tc = time.perf_counter()
+        y = oracle.alora_rows(x, W, A, B, w.token_adapter_ids, act, rows)
+        secs = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": len(rows) / secs, "unit": "tokens/s", "cores": min(threads, len(rows)),
+                               "kind": "oracle", "seconds": secs,
+                               "sample": f"{len(rows)} of {w.T} token rows (activation boundaries +-2, segment "
+                                         f"ends, evenly spaced rest), full projection + LoRA per row, fp64"}
+        # parity of the timed GPU result on the same sample
+        q = to_f64(db.q[torch.from_numpy(rows.astype(np.int64)).to("cuda")])
+        out["parity_sample_max_rel_err_q"] = maxnorm_rel(q, y[:, : w.Nq])
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -183,6 +183,25 @@ def assemble(name: str, dtype: str, hidden: int, n_q_heads: int, n_kv_heads: int
     return w
 
 
+def sample_rows(w: Workload, n: int) -> np.ndarray:
+    """Rows the oracle is timed/checked on: every segment's activation boundary +-2, first and last
+    row of every segment, then evenly spaced rows up to n."""
+    must = set()
+    t0 = 0
+    for s in w.segments:
+        t1 = t0 + s.n_tokens
+        must.update((t0, t1 - 1))
+        b = t0 + (s.activation_start - s.first_pos)
+        for d in range(-2, 3):
+            if t0 <= b + d < t1:
+                must.add(b + d)
+        t0 = t1
+    must = sorted(must)[:n]
+    rest = [int(t) for t in np.linspace(0, w.T - 1, num=max(n - len(must), 0), dtype=np.int64)]
+    return np.array(sorted(set(must) | set(rest)), dtype=np.int32)
+
+
+
 # --------------------------------------------------------------------------------------
 # the five benchmark configurations
 # --------------------------------------------------------------------------------------
