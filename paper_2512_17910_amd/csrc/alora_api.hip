@@ -36,6 +36,8 @@ static int check_dims(const alora_dims *d)
     if (d->dtype == ALORA_BF16) {
         if (d->hidden % 64 || Nq % 8 || Nkv % 8) return ALORA_ESHAPE;
         if (d->n_adapters > 0 && d->rank % 8) return ALORA_ESHAPE;
+        // 32-bit byte offsets inside the weight matrix (buffer addressing)
+        if ((long long)d->hidden * (Nq + 2 * Nkv) * 2 >= (1ll << 31)) return ALORA_ESHAPE;
     } else {
         if (d->hidden % 4 || Nq % 4 || Nkv % 4) return ALORA_ESHAPE;
     }

@@ -1,7 +1,7 @@
 // Fused bf16 projection kernel: base GEMM on bf16 MFMA (fp32 accumulate) with the low-rank
 // expand, the per-row activation select, the q_out store and the paged K/V store in one pass.
 //
-// Per 256(token) x 256(feature) tile:
+// Per 256(token) x 256(feature) tile, one workgroup of four wavefronts (one per SIMD):
 //   1. classify the tile's rows (App. B mask); list the adapters its adapted rows use
 //   2. expand first: for each such adapter a, accumulate [S_hi | S_lo](rows of a, else 0) . [B_a ; B_a]
 //      as extra K-slices of the same MFMA loop, then zero the accumulators of rows that are not
@@ -11,21 +11,29 @@
 //   4. round once to bf16 and store: columns [0,Nq) to q_out, K and V columns to the slot the
 //      row maps to (rows with slot -1 write no K/V)
 //
-// MFMA operand roles are swapped (weights are the "A" operand, tokens the "B" operand), so each
-// lane owns one token row per 32x32 block and four consecutive features per register quad:
-// the select is a per-lane condition and stores are 8-byte vectors.
-// LDS tiles are [row][64 k] bf16 with a 16-byte-chunk XOR swizzle; the weight tile is
-// transposed in registers (k-major global layout -> k-contiguous LDS rows) on its way in.
+// Data movement (gfx950):
+//   - global -> LDS with buffer loads that write LDS directly (no VGPR staging); the buffer
+//     descriptor's range check returns zeros for token rows past T, masked lanes get an
+//     out-of-range offset.  Two LDS stages of 64 KB; one barrier per 64-wide K-slice.
+//   - token tile in LDS: [row][64 k], 16-byte chunks XOR-swizzled by (row/2)%8, read with
+//     ds_read_b128.  Weight tile in LDS: k-major exactly as in global memory ([k][256 n]),
+//     16-byte chunks XOR-swizzled by 4*(k%4), read with the transposing LDS load
+//     (ds_read_b64_tr_b16), which hands each lane four consecutive k of one feature column.
+//   - MFMA operand roles are swapped (weights are "A", tokens are "B"): each lane owns one token
+//     row per 32x32 block and four consecutive features per register quad, so the select is a
+//     per-lane condition and stores are 8-byte vectors.
 #include "alora_internal.h"
 
 namespace alora {
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 256;
+constexpr uint32_t STAGE_BYTES = 65536, W_OFF = 32768;
+constexpr uint32_t OOR = 0x80000000u;  // buffer offset that is out of range for every descriptor
 
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 7; }
-// byte offset of 16-byte chunk c (k = 8c..8c+7) of tile row `row`
-__device__ __forceinline__ int lds_off(int row, int c) { return row * (BK * 2) + ((c ^ swz(row)) << 4); }
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
 struct GemmArgs {
     const bf16_t *x, *W, *S_hl;
@@ -36,31 +44,45 @@ struct GemmArgs {
     int mtiles, ntiles;
 };
 
-// Source of a K-slice: either the base operands (x rows, W rows k0..k0+63) or one adapter's
-// expand operands (S_hl rows masked to the adapter's rows, B rows (k mod r) for k < 2r).
-struct Slice {
-    const bf16_t *xsrc;  // row-major, leading dimension xld
-    int xld;
-    int xk_valid;        // columns >= xk_valid read as zero
-    int row_key;         // -2: every in-range row is valid; else only rows whose adapter == row_key
-    const bf16_t *wsrc;  // row-major [*, N]
-    int w_rows;          // k >= w_rows read as zero
-    int w_mod;           // 0: source row = k; else source row = k mod w_mod
-};
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, lds_byte *dst, uint32_t voffset,
+                                           uint32_t soffset)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)dst, 16, voffset,
+                                             soffset, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p)
+{
+    // k..k+3 of this lane's feature column, then k+4..k+7 (four rows of 512 bytes further on)
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * BN * 2));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
 
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *Xs = smem;                  // [BM][BK] bf16, swizzled  (32 KB)
-    unsigned char *Ws = smem + BM * BK * 2;    // [BN][BK] bf16, swizzled  (32 KB)
-    int *arow = (int *)(smem + (BM + BN) * BK * 2);  // [BM] effective adapter per tile row
-    int *present = arow + BM;                        // [ALORA_MAX_ADAPTERS]
+    // two separate LDS objects, so that the compiler can tell that reads of one stage do not
+    // depend on the in-flight direct loads into the other
+    __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE_BYTES];
+    __shared__ int arow[BM];                       // effective adapter per tile row
+    __shared__ int present[ALORA_MAX_ADAPTERS];
+    lds_byte *const st0 = (lds_byte *)stage0;
+    lds_byte *const st1 = (lds_byte *)stage1;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mt = blockIdx.x % g.mtiles, nt = blockIdx.x / g.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
-    const int wt = w & 1, wn = w >> 1;         // wave owns tokens [wt*128,+128) x features [wn*128,+128)
+    const int wt = w & 1, wn = w >> 1;   // wave owns tokens [wt*128,+128) x features [wn*128,+128)
     const int li = lane & 31, lh = lane >> 5;
+    const int rows_valid = min(g.T - m0, BM);
 
     // ---- 1. classify rows, list adapters --------------------------------------------------
     {
@@ -74,7 +96,40 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         __syncthreads();
     }
 
-    f32x16 acc[4][4];  // [feature tile][token tile]
+    // ---- per-lane constants of the global -> LDS copies ------------------------------------
+    // token tile: instruction ii of wave w fills rows 64w + 8ii .. +7; lane -> row +lane/8, physical
+    // chunk lane%8, which holds logical chunk (lane%8) ^ swizzle(row)
+    int xrow[8], xchunk[8];
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+        xrow[ii] = 64 * w + 8 * ii + (lane >> 3);
+        xchunk[ii] = (lane & 7) ^ ((xrow[ii] >> 1) & 7);
+    }
+    // weight tile: instruction jj of wave w fills k rows 16w + 2jj, +1; lane -> row +lane/32, physical
+    // chunk lane%32 holding logical chunk (lane%32) ^ 4*(k%4)
+    int wk[8], wchunk[8];
+    bool wcol_ok[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+        wk[jj] = 16 * w + 2 * jj + (lane >> 5);
+        wchunk[jj] = (lane & 31) ^ ((wk[jj] & 3) << 2);
+        wcol_ok[jj] = n0 + 8 * wchunk[jj] < g.N;
+    }
+
+    // ---- per-lane LDS read addresses of the MFMA operands ----------------------------------
+    uint32_t xaddr;  // token fragment: row wt*128 + li (+32 b), chunk 2ks + lh
+    {
+        const int row0 = wt * 128 + li;
+        xaddr = (uint32_t)row0 * (BK * 2) + (uint32_t)((lh ^ ((row0 >> 1) & 7)) << 4);
+    }
+    uint32_t waddr;  // weight fragment via transposing read; see read_w_frag
+    {
+        const int s = lane & 15, j = s >> 2, blk = (lane >> 4) & 1;
+        const int chunk = wn * 16 + 2 * blk + ((s & 3) >> 1);
+        waddr = W_OFF + (uint32_t)(8 * lh + j) * (BN * 2) + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s & 1) << 3);
+    }
+
+    f32x16 acc[4][4];  // [feature tile a][token tile b]
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -82,61 +137,25 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-    // global -> register staging of one K-slice
-    u32x4 xreg[8], wreg[8];
-    const int xc = tid & 7, xr0 = tid >> 3;                        // x tile: chunk xc of rows xr0 + 32 i
-    const int wnb = tid & 7, wkb = (tid >> 3) & 7, wq = tid >> 6;  // W tile: 8k x 8n block
-    const int wcol = n0 + wq * 64 + wnb * 8;
-
-    auto load_slice = [&](const Slice &s, int k0) {
+    auto issue = [&](__amdgpu_buffer_rsrc_t rx, const uint32_t (&vx)[8], uint32_t sx, __amdgpu_buffer_rsrc_t rw,
+                     const uint32_t (&vw)[8], uint32_t sw, lds_byte *st) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = xr0 + 32 * i;
-            const int t = m0 + row;
-            bool ok = (t < g.T) && (k0 + xc * 8 < s.xk_valid);
-            if (s.row_key != -2) ok = ok && (arow[row] == s.row_key);
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4 *)(s.xsrc + (size_t)t * s.xld + k0 + xc * 8);
-            xreg[i] = v;
-        }
+        for (int ii = 0; ii < 8; ++ii)
+            load_lds16(rx, st + (uint32_t)(64 * w + 8 * ii) * (BK * 2), vx[ii], sx);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int k = k0 + wkb * 8 + i;
-            const bool ok = (k < s.w_rows) && (wcol < g.N);
-            const int srow = (s.w_mod && k >= s.w_mod) ? k - s.w_mod : k;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4 *)(s.wsrc + (size_t)srow * g.N + wcol);
-            wreg[i] = v;
-        }
+        for (int jj = 0; jj < 8; ++jj)
+            load_lds16(rw, st + W_OFF + (uint32_t)(16 * w + 2 * jj) * (BN * 2), vw[jj], sw);
     };
 
-    auto store_slice = [&]() {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4 *)(Xs + lds_off(xr0 + 32 * i, xc)) = xreg[i];
-        // 8x8 transpose of 16-bit elements: out[j] = (row0[j], row1[j], ..., row7[j])
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 o;
-            o.x = __builtin_amdgcn_perm(wreg[1][j >> 1], wreg[0][j >> 1], sel);
-            o.y = __builtin_amdgcn_perm(wreg[3][j >> 1], wreg[2][j >> 1], sel);
-            o.z = __builtin_amdgcn_perm(wreg[5][j >> 1], wreg[4][j >> 1], sel);
-            o.w = __builtin_amdgcn_perm(wreg[7][j >> 1], wreg[6][j >> 1], sel);
-            *(u32x4 *)(Ws + lds_off(wq * 64 + wnb * 8 + j, wkb)) = o;
-        }
-    };
-
-    auto compute_slice = [&]() {
+    auto compute = [&](const lds_byte *base) {
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            const int c = 2 * ks + lh;
             bf16x8 wf[4], xf[4];
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-                wf[a] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(Ws + lds_off(wn * 128 + a * 32 + li, c)));
-#pragma unroll
             for (int b = 0; b < 4; ++b)
-                xf[b] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(Xs + lds_off(wt * 128 + b * 32 + li, c)));
+                xf[b] = *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
+#pragma unroll
+            for (int a = 0; a < 4; ++a) wf[a] = read_w_frag(base + ((waddr ^ (a << 6)) + ks * 16 * BN * 2));
 #pragma unroll
             for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -147,18 +166,35 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     // ---- 2. expand first, then select ------------------------------------------------------
     bool any_adapter = false;
-    for (int a = 0; a < g.L; ++a) {
-        if (!present[a]) continue;  // uniform (LDS broadcast)
-        any_adapter = true;
-        Slice s;
-        s.xsrc = g.S_hl; s.xld = 2 * g.r; s.xk_valid = 2 * g.r; s.row_key = a;
-        s.wsrc = (const bf16_t *)B.p[a]; s.w_rows = 2 * g.r; s.w_mod = g.r;
-        for (int k0 = 0; k0 < 2 * g.r; k0 += BK) {
-            load_slice(s, k0);
-            store_slice();
-            __syncthreads();
-            compute_slice();
-            __syncthreads();
+    if (g.L > 0) {
+        const __amdgpu_buffer_rsrc_t rs =
+            make_rsrc(g.S_hl + (size_t)m0 * 2 * g.r, (uint32_t)rows_valid * 2 * g.r * 2);
+        for (int a = 0; a < g.L; ++a) {
+            if (!present[a]) continue;  // uniform (LDS broadcast)
+            any_adapter = true;
+            const __amdgpu_buffer_rsrc_t rb =
+                make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(g.r * g.N - n0) * 2);
+            for (int k0 = 0; k0 < 2 * g.r; k0 += BK) {
+                uint32_t vx[8], vw[8];
+#pragma unroll
+                for (int ii = 0; ii < 8; ++ii) {
+                    const int kk = k0 + 8 * xchunk[ii];
+                    const bool ok = arow[xrow[ii]] == a && kk < 2 * g.r;
+                    vx[ii] = ok ? (uint32_t)(xrow[ii] * 2 * g.r + kk) * 2 : OOR;
+                }
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int kk = k0 + wk[jj];
+                    const int srow = kk >= g.r ? kk - g.r : kk;
+                    const bool ok = kk < 2 * g.r && wcol_ok[jj];
+                    vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * wchunk[jj]) * 2 : OOR;
+                }
+                issue(rs, vx, 0, rb, vw, 0, st0);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                compute(st0);
+                __syncthreads();
+            }
         }
     }
     if (any_adapter) {
@@ -174,16 +210,27 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     // ---- 3. base GEMM ---------------------------------------------------------------------
     {
-        Slice s;
-        s.xsrc = g.x; s.xld = g.H; s.xk_valid = g.H; s.row_key = -2;
-        s.wsrc = g.W; s.w_rows = g.H; s.w_mod = 0;
-        load_slice(s, 0);
-        for (int k0 = 0; k0 < g.H; k0 += BK) {
-            store_slice();
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
+        const __amdgpu_buffer_rsrc_t rw = make_rsrc(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
+        uint32_t vx[8], vw[8];
+#pragma unroll
+        for (int ii = 0; ii < 8; ++ii) vx[ii] = (uint32_t)(xrow[ii] * g.H + 8 * xchunk[ii]) * 2;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) vw[jj] = wcol_ok[jj] ? (uint32_t)(wk[jj] * g.N + 8 * wchunk[jj]) * 2 : OOR;
+        const int KT = g.H / BK;
+        const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
+        issue(rx, vx, 0, rw, vw, 0, st0);
+        for (int kt = 0; kt < KT; kt += 2) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (k0 + BK < g.H) load_slice(s, k0 + BK);
-            compute_slice();
-            __syncthreads();
+            if (kt + 1 < KT) issue(rx, vx, (kt + 1) * xstep, rw, vw, (kt + 1) * wstep, st1);
+            compute(st0);
+            if (kt + 1 < KT) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (kt + 2 < KT) issue(rx, vx, (kt + 2) * xstep, rw, vw, (kt + 2) * wstep, st0);
+                compute(st1);
+            }
         }
     }
 
@@ -229,15 +276,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
     g.T = f.T; g.H = f.H; g.Nq = f.Nq; g.Nkv = f.Nkv; g.N = f.N; g.L = f.L; g.r = f.r;
     g.mtiles = (f.T + BM - 1) / BM;
     g.ntiles = (f.N + BN - 1) / BN;
-    const size_t smem = (size_t)(BM + BN) * BK * 2 + (BM + ALORA_MAX_ADAPTERS) * sizeof(int);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)alora_gemm_bf16_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return (int)e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(alora_gemm_bf16_kernel, dim3(g.mtiles * g.ntiles), dim3(GEMM_THREADS), smem, f.stream, g, B);
+    hipLaunchKernelGGL(alora_gemm_bf16_kernel, dim3(g.mtiles * g.ntiles), dim3(GEMM_THREADS), 0, f.stream, g, B);
     return (int)hipGetLastError();
 }
 
