@@ -19,7 +19,8 @@ static Profile g_prof;
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t active, perm, offsets, S, partial, total;
+    size_t active, perm, offsets, S, blocktab, total;
+    int n_blocks;
 };
 
 static int check_dims(const alora_dims *d)
@@ -52,10 +53,10 @@ static Layout make_layout(const alora_dims *d)
     l.active = o;  o += up256(T);
     l.perm = o;    o += up256(4 * T);
     l.offsets = o; o += up256(4 * (L + 1));
-    l.S = o;       o += up256(T * r * 4);  // f32: [T,r] fp32; bf16: [T,2r] bf16
-    l.partial = o;
-    if (d->dtype == ALORA_BF16)
-        o += up256(bf16_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
+    // f32: [T,r] fp32; bf16: [T, slices, 2r] bf16 (hi | lo halves of every hidden-dimension slice)
+    l.S = o;       o += up256(d->dtype == ALORA_BF16 ? T * r * 4 * (size_t)shrink_slices(d->hidden, d->rank ? d->rank : 8) : T * r * 4);
+    l.n_blocks = L > 0 ? shrink_blocks(d->T, d->n_adapters) : 0;
+    l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
     l.total = std::max<size_t>(o, 256);
     return l;
 }
@@ -80,7 +81,8 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
     f.perm = (int32_t *)(b + l.perm);
     f.offsets = (int32_t *)(b + l.offsets);
     f.S = b + l.S;
-    f.partial = (float *)(b + l.partial);
+    f.blocktab = (int4 *)(b + l.blocktab);
+    f.n_blocks = l.n_blocks;
     f.stream = (hipStream_t)stream;
 }
 

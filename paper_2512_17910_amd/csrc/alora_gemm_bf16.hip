@@ -1,10 +1,10 @@
 // Fused bf16 projection kernel: base GEMM on bf16 MFMA (fp32 accumulate) with the low-rank
 // expand, the per-row activation select, the q_out store and the paged K/V store in one pass.
 //
-// Per 256(token) x 256(feature) tile, one workgroup of four wavefronts (one per SIMD):
+// Per 256(token) x 256|192|128(feature) tile, one workgroup of four wavefronts (one per SIMD):
 //   1. classify the tile's rows (App. B mask); list the adapters its adapted rows use
-//   2. expand first: for each such adapter a, accumulate [S_hi | S_lo](rows of a, else 0) . [B_a ; B_a]
-//      as extra K-slices of the same MFMA loop, then zero the accumulators of rows that are not
+//   2. expand first: for each such adapter a, accumulate [S_hi | S_lo | ...](rows of a, else 0) . [B_a ; B_a ; ...]
+//      (one hi/lo pair per hidden-dimension slice of the shrink) as extra K-slices of the same MFMA loop, then zero the accumulators of rows that are not
 //      adapted (a select, not a multiply: adapter data never reaches a base row)
 //   3. base GEMM over the hidden dimension: rows that are not adapted see exactly the
 //      instruction sequence of a call without adapters, so they come out bit-identical to it
@@ -26,7 +26,8 @@
 
 namespace alora {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BK = 64;
+constexpr int WPITCH = 512;  // bytes per k row of the weight tile in LDS (room for 256 features)
 constexpr int GEMM_THREADS = 256;
 constexpr uint32_t STAGE_BYTES = 65536, W_OFF = 32768;
 constexpr uint32_t OOR = 0x80000000u;  // buffer offset that is out of range for every descriptor
@@ -41,6 +42,7 @@ struct GemmArgs {
     const int64_t *slot;
     bf16_t *q, *kc, *vc;
     int T, H, Nq, Nkv, N, L, r;
+    int kx;  // length of the expand's K dimension: hidden-dimension slices of the shrink x (hi | lo) x r
     int mtiles, ntiles;
 };
 
@@ -60,13 +62,16 @@ __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p)
 {
     // k..k+3 of this lane's feature column, then k+4..k+7 (four rows of 512 bytes further on)
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * BN * 2));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * WPITCH));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// NTW: 32-wide feature tiles per wavefront; the workgroup tile is 256 tokens x 64*NTW features
+template <int NTW>
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B)
 {
+    constexpr int BN = 64 * NTW;
     // two separate LDS objects, so that the compiler can tell that reads of one stage do not
     // depend on the in-flight direct loads into the other
     __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE_BYTES];
@@ -80,7 +85,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mt = blockIdx.x % g.mtiles, nt = blockIdx.x / g.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
-    const int wt = w & 1, wn = w >> 1;   // wave owns tokens [wt*128,+128) x features [wn*128,+128)
+    const int wt = w & 1, wn = w >> 1;   // wave owns tokens [wt*128,+128) x features [wn*32*NTW,+32*NTW)
     const int li = lane & 31, lh = lane >> 5;
     const int rows_valid = min(g.T - m0, BM);
 
@@ -113,7 +118,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     for (int jj = 0; jj < 8; ++jj) {
         wk[jj] = 16 * w + 2 * jj + (lane >> 5);
         wchunk[jj] = (lane & 31) ^ ((wk[jj] & 3) << 2);
-        wcol_ok[jj] = n0 + 8 * wchunk[jj] < g.N;
+        wcol_ok[jj] = 8 * wchunk[jj] < BN && n0 + 8 * wchunk[jj] < g.N;
     }
 
     // ---- per-lane LDS read addresses of the MFMA operands ----------------------------------
@@ -122,16 +127,19 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         const int row0 = wt * 128 + li;
         xaddr = (uint32_t)row0 * (BK * 2) + (uint32_t)((lh ^ ((row0 >> 1) & 7)) << 4);
     }
-    uint32_t waddr;  // weight fragment via transposing read; see read_w_frag
+    uint32_t waddr[NTW];  // weight fragments via transposing read; see read_w_frag
     {
         const int s = lane & 15, j = s >> 2, blk = (lane >> 4) & 1;
-        const int chunk = wn * 16 + 2 * blk + ((s & 3) >> 1);
-        waddr = W_OFF + (uint32_t)(8 * lh + j) * (BN * 2) + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s & 1) << 3);
+#pragma unroll
+        for (int a = 0; a < NTW; ++a) {
+            const int chunk = wn * 4 * NTW + 4 * a + 2 * blk + ((s & 3) >> 1);
+            waddr[a] = W_OFF + (uint32_t)(8 * lh + j) * WPITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s & 1) << 3);
+        }
     }
 
-    f32x16 acc[4][4];  // [feature tile a][token tile b]
+    f32x16 acc[NTW][4];  // [feature tile a][token tile b]
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < NTW; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -144,49 +152,75 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             load_lds16(rx, st + (uint32_t)(64 * w + 8 * ii) * (BK * 2), vx[ii], sx);
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj)
-            load_lds16(rw, st + W_OFF + (uint32_t)(16 * w + 2 * jj) * (BN * 2), vw[jj], sw);
+            load_lds16(rw, st + W_OFF + (uint32_t)(16 * w + 2 * jj) * WPITCH, vw[jj], sw);
     };
 
+    // MFMA fragments of one 16-wide k step
+    auto load_frags = [&](const lds_byte *base, int ks, bf16x8 (&wf)[NTW], bf16x8 (&xf)[4]) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            xf[b] = *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
+#pragma unroll
+        for (int a = 0; a < NTW; ++a) wf[a] = read_w_frag(base + (waddr[a] + ks * 16 * WPITCH));
+    };
+    // one 64-wide K-slice out of LDS; the fragments of step ks+1 are fetched before the MFMAs of
+    // step ks are issued, so LDS latency hides behind the matrix pipe
     auto compute = [&](const lds_byte *base) {
+        bf16x8 wf[2][NTW], xf[2][4];
+        load_frags(base, 0, wf[0], xf[0]);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 wf[4], xf[4];
+            if (ks + 1 < BK / 16) load_frags(base, ks + 1, wf[(ks + 1) & 1], xf[(ks + 1) & 1]);
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                xf[b] = *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
-#pragma unroll
-            for (int a = 0; a < 4; ++a) wf[a] = read_w_frag(base + ((waddr ^ (a << 6)) + ks * 16 * BN * 2));
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
+            for (int a = 0; a < NTW; ++a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b], 0, 0, 0);
         }
+    };
+    // Instruction order handed to the scheduler for one K-slice region (global->LDS copies of the
+    // next slice + the MFMAs of this one): first fragments and a few copies while they arrive,
+    // then one LDS read and one copy behind every MFMA, so neither queue blocks the matrix pipe.
+    auto pipeline_order = [&](bool with_copies) {
+        constexpr int NREAD = 4 + 2 * NTW, NMFMA = 4 * NTW;
+        int copies = with_copies ? 16 : 0;
+        __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);
+        if (copies) { __builtin_amdgcn_sched_group_barrier(0x020, 4, 0); copies -= 4; }
+#pragma unroll
+        for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+#pragma unroll
+            for (int i = 0; i < NMFMA; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i < NREAD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (copies > 0) { __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); --copies; }
+            }
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA, 0);
     };
 
     // ---- 2. expand first, then select ------------------------------------------------------
     bool any_adapter = false;
     if (g.L > 0) {
         const __amdgpu_buffer_rsrc_t rs =
-            make_rsrc(g.S_hl + (size_t)m0 * 2 * g.r, (uint32_t)rows_valid * 2 * g.r * 2);
+            make_rsrc(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
         for (int a = 0; a < g.L; ++a) {
             if (!present[a]) continue;  // uniform (LDS broadcast)
             any_adapter = true;
             const __amdgpu_buffer_rsrc_t rb =
                 make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(g.r * g.N - n0) * 2);
-            for (int k0 = 0; k0 < 2 * g.r; k0 += BK) {
+            for (int k0 = 0; k0 < g.kx; k0 += BK) {
                 uint32_t vx[8], vw[8];
 #pragma unroll
                 for (int ii = 0; ii < 8; ++ii) {
                     const int kk = k0 + 8 * xchunk[ii];
-                    const bool ok = arow[xrow[ii]] == a && kk < 2 * g.r;
-                    vx[ii] = ok ? (uint32_t)(xrow[ii] * 2 * g.r + kk) * 2 : OOR;
+                    const bool ok = arow[xrow[ii]] == a && kk < g.kx;
+                    vx[ii] = ok ? (uint32_t)(xrow[ii] * g.kx + kk) * 2 : OOR;
                 }
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) {
                     const int kk = k0 + wk[jj];
-                    const int srow = kk >= g.r ? kk - g.r : kk;
-                    const bool ok = kk < 2 * g.r && wcol_ok[jj];
+                    const int srow = kk % g.r;
+                    const bool ok = kk < g.kx && wcol_ok[jj];
                     vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * wchunk[jj]) * 2 : OOR;
                 }
                 issue(rs, vx, 0, rb, vw, 0, st0);
@@ -202,7 +236,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         for (int b = 0; b < 4; ++b) {
             const bool keep = arow[wt * 128 + b * 32 + li] >= 0;
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
+            for (int a = 0; a < NTW; ++a)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[a][b][e] = keep ? acc[a][b][e] : 0.f;
         }
@@ -220,18 +254,29 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         const int KT = g.H / BK;
         const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
         issue(rx, vx, 0, rw, vw, 0, st0);
+        // The copy of slice kt+1 is issued unconditionally inside the region that computes slice kt
+        // (past the end it re-reads the last slice into the idle stage), so that the scheduler can
+        // spread the copies between the MFMAs.
         for (int kt = 0; kt < KT; kt += 2) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (kt + 1 < KT) issue(rx, vx, (kt + 1) * xstep, rw, vw, (kt + 1) * wstep, st1);
-            compute(st0);
-            if (kt + 1 < KT) {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-                if (kt + 2 < KT) issue(rx, vx, (kt + 2) * xstep, rw, vw, (kt + 2) * wstep, st0);
+            {
+                const int kn = min(kt + 1, KT - 1);
+                issue(rx, vx, kn * xstep, rw, vw, kn * wstep, st1);
+                compute(st0);
+                pipeline_order(true);
+            }
+            if (kt + 1 >= KT) break;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            {
+                const int kn = min(kt + 2, KT - 1);
+                issue(rx, vx, kn * xstep, rw, vw, kn * wstep, st0);
                 compute(st1);
+                pipeline_order(true);
             }
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
     // ---- 4. round and store ------------------------------------------------------------------
@@ -245,10 +290,10 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         bf16_t *krow = g.kc + (size_t)(sl < 0 ? 0 : sl) * g.Nkv;
         bf16_t *vrow = g.vc + (size_t)(sl < 0 ? 0 : sl) * g.Nkv;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < NTW; ++a) {
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-                const int n = n0 + wn * 128 + a * 32 + 8 * gq + 4 * lh;
+                const int n = n0 + wn * 32 * NTW + a * 32 + 8 * gq + 4 * lh;
                 if (n >= g.N) continue;
                 u32x2 v;
                 v.x = f32_to_bf16_bits(acc[a][b][4 * gq + 0]) | (f32_to_bf16_bits(acc[a][b][4 * gq + 1]) << 16);
@@ -264,8 +309,6 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     }
 }
 
-size_t bf16_partial_bytes(int, int, int) { return 0; }
-
 int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
 {
     if (f.T == 0) return 0;
@@ -274,9 +317,32 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
     g.aid = f.aid; g.seg = f.seg; g.pos = f.pos; g.start = f.start; g.slot = f.slot;
     g.q = (bf16_t *)f.q; g.kc = (bf16_t *)f.kc; g.vc = (bf16_t *)f.vc;
     g.T = f.T; g.H = f.H; g.Nq = f.Nq; g.Nkv = f.Nkv; g.N = f.N; g.L = f.L; g.r = f.r;
+    g.kx = f.L > 0 ? shrink_slices(f.H, f.r) * 2 * f.r : 0;
     g.mtiles = (f.T + BM - 1) / BM;
-    g.ntiles = (f.N + BN - 1) / BN;
-    hipLaunchKernelGGL(alora_gemm_bf16_kernel, dim3(g.mtiles * g.ntiles), dim3(GEMM_THREADS), 0, f.stream, g, B);
+    // Feature-tile width: the one that needs the least time on `cus` compute units, counting whole
+    // rounds of one workgroup per unit (a narrower tile costs a little more per flop).  It depends
+    // on the call's sizes only, never on adapter data, so a call without adapters tiles alike.
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    int best_ntw = 4;
+    double best_cost = 1e300;
+    const int cand[3] = {4, 3, 2};
+    const double unit[3] = {1.0, 0.78, 0.56};
+    for (int i = 0; i < 3; ++i) {
+        const long tiles = (long)g.mtiles * ((f.N + 64 * cand[i] - 1) / (64 * cand[i]));
+        const double cost = (double)((tiles + cus - 1) / cus) * unit[i];
+        if (cost < best_cost - 1e-9) { best_cost = cost; best_ntw = cand[i]; }
+    }
+    g.ntiles = (f.N + 64 * best_ntw - 1) / (64 * best_ntw);
+    const dim3 grid(g.mtiles * g.ntiles), block(GEMM_THREADS);
+    if (best_ntw == 4) hipLaunchKernelGGL(alora_gemm_bf16_kernel<4>, grid, block, 0, f.stream, g, B);
+    else if (best_ntw == 3) hipLaunchKernelGGL(alora_gemm_bf16_kernel<3>, grid, block, 0, f.stream, g, B);
+    else hipLaunchKernelGGL(alora_gemm_bf16_kernel<2>, grid, block, 0, f.stream, g, B);
     return (int)hipGetLastError();
 }
 

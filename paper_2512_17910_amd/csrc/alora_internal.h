@@ -31,8 +31,9 @@ struct Fwd {
     // workspace regions
     uint8_t *active;
     int32_t *perm, *offsets;
-    void *S;          // bf16: [T,2r] bf16 (hi | lo halves of the fp32 shrink result); f32: [T,r] fp32
-    float *partial;   // split-K partial sums of the decode-shaped path (bf16 only)
+    void *S;          // bf16: [T, slices, 2r] bf16 (hi | lo halves per hidden-dimension slice); f32: [T,r] fp32
+    int4 *blocktab;      // shrink: (adapter, first perm index, rows, 0) per 32-row block; adapter -1 = unused
+    int n_blocks;        // entries in blocktab (upper bound on 32-row blocks)
     hipStream_t stream;
 };
 
@@ -62,6 +63,7 @@ int launch_shrink_f32(const Fwd &f, const PtrTable &A);
 int launch_gemm_f32(const Fwd &f, const PtrTable &B);
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A);
 int launch_gemm_bf16(const Fwd &f, const PtrTable &B);
-size_t bf16_partial_bytes(int T, int H, int N);
+int shrink_blocks(int T, int L);
+int shrink_slices(int H, int r);
 
 }  // namespace alora
