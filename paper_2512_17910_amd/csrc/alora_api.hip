@@ -19,7 +19,7 @@ static Profile g_prof;
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t active, perm, offsets, S, blocktab, total;
+    size_t active, aeff, perm, offsets, S, blocktab, total;
     int n_blocks;
 };
 
@@ -51,6 +51,7 @@ static Layout make_layout(const alora_dims *d)
     const size_t T = (size_t)d->T, L = (size_t)d->n_adapters, r = (size_t)d->rank;
     size_t o = 0;
     l.active = o;  o += up256(T);
+    l.aeff = o;    o += up256(T);
     l.perm = o;    o += up256(4 * T);
     l.offsets = o; o += up256(4 * (L + 1));
     // f32: [T,r] fp32; bf16: [T, slices, 2r] bf16 (hi | lo halves of every hidden-dimension slice)
@@ -78,6 +79,7 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
     f.seg = d->token_seg_ids; f.pos = d->token_positions;
     unsigned char *b = (unsigned char *)ws;
     f.active = b + l.active;
+    f.aeff = (int8_t *)(b + l.aeff);
     f.perm = (int32_t *)(b + l.perm);
     f.offsets = (int32_t *)(b + l.offsets);
     f.S = b + l.S;

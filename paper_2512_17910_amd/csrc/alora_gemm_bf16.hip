@@ -34,11 +34,13 @@ constexpr uint32_t OOR = 0x80000000u;  // buffer offset that is out of range for
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
 struct GemmArgs {
     const bf16_t *x, *W, *S_hl;
-    const int32_t *aid, *seg, *pos, *start;
+    const int8_t *aeff;   // per token: adapter id if the row is adapted, else -1 (grouping kernel)
     const int64_t *slot;
     bf16_t *q, *kc, *vc;
     int T, H, Nq, Nkv, N, L, r;
@@ -78,6 +80,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE_BYTES];
     __shared__ int arow[BM];                       // effective adapter per tile row
     __shared__ int present[ALORA_MAX_ADAPTERS];
+    __shared__ int64_t slot_lds[BM];               // cache slot per tile row (-1: no K/V write)
     lds_byte *const st0 = (lds_byte *)stage0;
     lds_byte *const st1 = (lds_byte *)stage1;
 
@@ -89,11 +92,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     const int li = lane & 31, lh = lane >> 5;
     const int rows_valid = min(g.T - m0, BM);
 
-    // ---- 1. classify rows, list adapters --------------------------------------------------
+    // ---- 1. this tile's rows: effective adapter (from the grouping kernel), cache slot; adapters present
     {
         const int t = m0 + tid;
         int a = -1;
-        if (t < g.T && g.L > 0) a = effective_adapter(g.aid, g.seg, g.pos, g.start, t);
+        if (t < g.T && g.L > 0) a = g.aeff[t];
+        slot_lds[tid] = t < g.T ? g.slot[t] : -1;
         arow[tid] = a;
         if (tid < ALORA_MAX_ADAPTERS) present[tid] = 0;
         __syncthreads();
@@ -280,29 +284,50 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     }
 
     // ---- 4. round and store ------------------------------------------------------------------
-    // D[i][j]: i = feature (8g + 4*lh + jj, register 4g + jj), j = token (li)
+    // D[i][j]: i = feature (8g + 4*lh + jj, register 4g + jj), j = token (li).  Each wavefront turns
+    // its 128 x 32*NTW block around through a private LDS strip, 32 token rows at a time (8-byte
+    // writes of four consecutive features, 16-byte reads along the row), so that global stores are
+    // whole row segments: 64*NTW contiguous bytes of q_out or of one cache slot per token.
+    __syncthreads();  // every wavefront has finished reading the K-slice stages
+    {
+        constexpr int EP = 64 * NTW + 16;      // strip row pitch in bytes
+        constexpr int LPR = 4 * NTW;           // lanes per row (16 bytes each)
+        constexpr int RPI = 64 / LPR;          // rows per store instruction
+        lds_byte *strip = st0 + w * 16384;
+        const int er = lane / LPR, ec = lane % LPR;
+        const int n = n0 + wn * 32 * NTW + ec * 8;
+        // destination of this lane's 8 features: 0 = q_out, 1 = K cache, 2 = V cache, -1 = none
+        int region = -1, col = 0;
+        if (er < RPI && n < g.N) {
+            if (n < g.Nq) { region = 0; col = n; }
+            else if (n < g.Nq + g.Nkv) { region = 1; col = n - g.Nq; }
+            else { region = 2; col = n - g.Nq - g.Nkv; }
+        }
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int t = m0 + wt * 128 + b * 32 + li;
-        if (t >= g.T) continue;
-        const int64_t sl = g.slot[t];
-        bf16_t *qrow = g.q + (size_t)t * g.Nq;
-        bf16_t *krow = g.kc + (size_t)(sl < 0 ? 0 : sl) * g.Nkv;
-        bf16_t *vrow = g.vc + (size_t)(sl < 0 ? 0 : sl) * g.Nkv;
+        for (int b = 0; b < 4; ++b) {
 #pragma unroll
-        for (int a = 0; a < NTW; ++a) {
+            for (int a = 0; a < NTW; ++a) {
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int n = n0 + wn * 32 * NTW + a * 32 + 8 * gq + 4 * lh;
-                if (n >= g.N) continue;
-                u32x2 v;
-                v.x = f32_to_bf16_bits(acc[a][b][4 * gq + 0]) | (f32_to_bf16_bits(acc[a][b][4 * gq + 1]) << 16);
-                v.y = f32_to_bf16_bits(acc[a][b][4 * gq + 2]) | (f32_to_bf16_bits(acc[a][b][4 * gq + 3]) << 16);
-                if (n < g.Nq) {
-                    *(u32x2 *)(qrow + n) = v;
-                } else if (sl >= 0) {
-                    if (n < g.Nq + g.Nkv) *(u32x2 *)(krow + (n - g.Nq)) = v;
-                    else *(u32x2 *)(vrow + (n - g.Nq - g.Nkv)) = v;
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x2 p0 = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1]};
+                    const f32x2 p1 = {acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
+                    u32x2 v;
+                    v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2));
+                    v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2));
+                    *(__attribute__((address_space(3))) u32x2 *)(strip + li * EP + (a * 32 + 8 * gq + 4 * lh) * 2) = v;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < (32 + RPI - 1) / RPI; ++i) {
+                const int r = i * RPI + er;
+                const int row = wt * 128 + b * 32 + r;
+                if (region < 0 || r >= 32 || m0 + row >= g.T) continue;
+                const u32x4 v = *(const __attribute__((address_space(3))) u32x4 *)(strip + r * EP + ec * 16);
+                if (region == 0) {
+                    *(u32x4 *)(g.q + (size_t)(m0 + row) * g.Nq + col) = v;
+                } else {
+                    const int64_t sl = slot_lds[row];
+                    if (sl >= 0) *(u32x4 *)((region == 1 ? g.kc : g.vc) + (size_t)sl * g.Nkv + col) = v;
                 }
             }
         }
@@ -314,7 +339,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
     if (f.T == 0) return 0;
     GemmArgs g;
     g.x = (const bf16_t *)f.x; g.W = (const bf16_t *)f.W; g.S_hl = (const bf16_t *)f.S;
-    g.aid = f.aid; g.seg = f.seg; g.pos = f.pos; g.start = f.start; g.slot = f.slot;
+    g.aeff = f.aeff; g.slot = f.slot;
     g.q = (bf16_t *)f.q; g.kc = (bf16_t *)f.kc; g.vc = (bf16_t *)f.vc;
     g.T = f.T; g.H = f.H; g.Nq = f.Nq; g.Nkv = f.Nkv; g.N = f.N; g.L = f.L; g.r = f.r;
     g.kx = f.L > 0 ? shrink_slices(f.H, f.r) * 2 * f.r : 0;

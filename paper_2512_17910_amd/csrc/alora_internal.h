@@ -30,6 +30,7 @@ struct Fwd {
     void *q, *kc, *vc;
     // workspace regions
     uint8_t *active;
+    int8_t *aeff;        // [T] adapter id of adapted rows, -1 for rows that keep the base output
     int32_t *perm, *offsets;
     void *S;          // bf16: [T, slices, 2r] bf16 (hi | lo halves per hidden-dimension slice); f32: [T,r] fp32
     int4 *blocktab;      // shrink: (adapter, first perm index, rows, 0) per 32-row block; adapter -1 = unused

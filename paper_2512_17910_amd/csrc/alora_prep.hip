@@ -21,6 +21,7 @@ template <bool CACHED>
 __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     const int32_t *__restrict__ aid, const int32_t *__restrict__ seg, const int32_t *__restrict__ pos,
     const int32_t *__restrict__ start, int T, int L, uint8_t *__restrict__ active,
+    int8_t *__restrict__ aeff_out,
     int32_t *__restrict__ perm, int32_t *__restrict__ offsets,
     int4 *__restrict__ blocktab, int n_blocks)
 {
@@ -57,6 +58,7 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
                 if (t < T) {
                     const int e = (a[u] >= 0 && p[u] >= start[s[u]]) ? a[u] : -1;
                     aeff[t] = (int8_t)e;
+                    aeff_out[t] = (int8_t)e;
                     active[t] = (uint8_t)(e >= 0);
                 }
             }
@@ -73,6 +75,7 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
                 a = aeff[t];
             } else {
                 a = effective_adapter(aid, seg, pos, start, t);
+                aeff_out[t] = (int8_t)a;
                 active[t] = (uint8_t)(a >= 0);
             }
         }
@@ -158,10 +161,10 @@ int launch_classify_group(const Fwd &f)
     if (f.T == 0) return 0;
     if (f.T <= PREP_CACHE_ROWS)
         hipLaunchKernelGGL(classify_group_kernel<true>, dim3(1), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg, f.pos,
-                           f.start, f.T, f.L, f.active, f.perm, f.offsets, f.blocktab, f.n_blocks);
+                           f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks);
     else
         hipLaunchKernelGGL(classify_group_kernel<false>, dim3(1), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg,
-                           f.pos, f.start, f.T, f.L, f.active, f.perm, f.offsets, f.blocktab, f.n_blocks);
+                           f.pos, f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks);
     return (int)hipGetLastError();
 }
 
