@@ -86,9 +86,11 @@ typedef struct alora_dims {
  * after alora_qkv_classify_group or alora_qkv_forward (byte offsets from its start). */
 typedef struct alora_ws_layout {
     size_t active_off;      /* uint8  [T]    1 = row receives its adapter's delta              */
-    size_t perm_off;        /* int32  [T]    first offsets[L] entries: active rows grouped by
-                                             adapter, increasing t inside a group (stable)     */
-    size_t offsets_off;     /* int32  [L+1]  group a is perm[offsets[a] .. offsets[a+1])        */
+    size_t perm_off;        /* int32  [T]    a permutation of the rows; first offsets[L] entries: active
+                                             rows grouped by adapter, increasing t inside a group  */
+    size_t offsets_off;     /* int32  [L+2]  group a is perm[offsets[a] .. offsets[a+1]); the rows that
+                                             keep the base output follow as one last group,
+                                             perm[offsets[L] .. offsets[L+1] = T), increasing t */
     size_t total_bytes;     /* same value alora_qkv_workspace_bytes reports                    */
 } alora_ws_layout;
 
@@ -139,6 +141,18 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
  */
 int alora_qkv_validate(const int32_t *token_adapter_ids, const int32_t *activation_start,
                        const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims);
+
+/*
+ * Tuning override for tests and benchmarks of the bf16 path (process-wide, not thread-safe; set it
+ * before querying the workspace size).  By default the library picks, from (T, hidden, N) alone,
+ * the width of the projection kernel's feature tile and, for batches too small to fill the chip,
+ * into how many splits of the hidden dimension the base product is cut (the small-batch path:
+ * split projection + a finishing kernel over the grouped rows).
+ *   feature_tiles  0 = automatic, else 2, 3 or 4: tile width 128, 192 or 256 features
+ *   splits         0 = automatic, 1 = never split, 2..8 = that many splits where the sizes allow
+ * Any setting computes the same result up to fp32 summation order.
+ */
+int alora_qkv_set_tuning(int feature_tiles, int splits);
 
 /*
  * Benchmark aid (not for serving loops: it creates HIP events).  Between _begin and _end, every

@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_validate.argtypes = [vp, vp, vp, i32, ctypes.POINTER(AloraDims)]
         L.alora_status_string.argtypes = [ctypes.c_int]
         L.alora_status_string.restype = ctypes.c_char_p
+        L.alora_qkv_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.alora_qkv_set_tuning.restype = ctypes.c_int
         L.alora_qkv_profile_begin.argtypes = [ctypes.c_int]
         L.alora_qkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
@@ -142,7 +144,7 @@ def workspace_int_views(dims: AloraDims, workspace):
     T, L = dims.T, dims.n_adapters
     active = workspace[lay.active_off: lay.active_off + T]
     perm = workspace[lay.perm_off: lay.perm_off + 4 * T].view(torch.int32)
-    offsets = workspace[lay.offsets_off: lay.offsets_off + 4 * (L + 1)].view(torch.int32)
+    offsets = workspace[lay.offsets_off: lay.offsets_off + 4 * (L + 2)].view(torch.int32)
     return active, perm, offsets
 
 
@@ -177,3 +179,10 @@ def alora_qkv_profile_end():
     if s:
         raise AloraError(s, "alora_qkv_profile_end")
     return float(ms.value), int(n.value)
+
+
+def alora_qkv_set_tuning(feature_tiles: int = 0, splits: int = 0) -> None:
+    """Override the automatic tiling of the bf16 path (0, 0 restores it); see alora_qkv.h."""
+    s = lib().alora_qkv_set_tuning(feature_tiles, splits)
+    if s:
+        raise AloraError(s, "alora_qkv_set_tuning")

@@ -19,7 +19,7 @@ static Profile g_prof;
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t active, aeff, perm, offsets, S, blocktab, total;
+    size_t active, aeff, perm, offsets, S, blocktab, partial, total;
     int n_blocks;
 };
 
@@ -53,11 +53,13 @@ static Layout make_layout(const alora_dims *d)
     l.active = o;  o += up256(T);
     l.aeff = o;    o += up256(T);
     l.perm = o;    o += up256(4 * T);
-    l.offsets = o; o += up256(4 * (L + 1));
+    l.offsets = o; o += up256(4 * (L + 2));
     // f32: [T,r] fp32; bf16: [T, slices, 2r] bf16 (hi | lo halves of every hidden-dimension slice)
     l.S = o;       o += up256(d->dtype == ALORA_BF16 ? T * r * 4 * (size_t)shrink_slices(d->hidden, d->rank ? d->rank : 8) : T * r * 4);
-    l.n_blocks = L > 0 ? shrink_blocks(d->T, d->n_adapters) : 0;
+    l.n_blocks = group_blocks(d->T, d->n_adapters);
     l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
+    l.partial = o;
+    if (d->dtype == ALORA_BF16) o += up256(gemm_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
     l.total = std::max<size_t>(o, 256);
     return l;
 }
@@ -84,6 +86,7 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
     f.offsets = (int32_t *)(b + l.offsets);
     f.S = b + l.S;
     f.blocktab = (int4 *)(b + l.blocktab);
+    f.partial = (float *)(b + l.partial);
     f.n_blocks = l.n_blocks;
     f.stream = (hipStream_t)stream;
 }
@@ -208,6 +211,14 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
         }
     }
     if (e) { g_last_hip_error = e; return ALORA_EHIP; }
+    return ALORA_OK;
+}
+
+int alora_qkv_set_tuning(int feature_tiles, int splits)
+{
+    if (feature_tiles != 0 && (feature_tiles < 2 || feature_tiles > 4)) return ALORA_EINVAL;
+    if (splits < 0 || splits > 8) return ALORA_EINVAL;
+    set_gemm_tuning(feature_tiles, splits);
     return ALORA_OK;
 }
 

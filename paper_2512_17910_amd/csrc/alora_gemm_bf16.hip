@@ -22,6 +22,7 @@
 //   - MFMA operand roles are swapped (weights are "A", tokens are "B"): each lane owns one token
 //     row per 32x32 block and four consecutive features per register quad, so the select is a
 //     per-lane condition and stores are 8-byte vectors.
+#include <algorithm>
 #include "alora_internal.h"
 
 namespace alora {
@@ -46,6 +47,8 @@ struct GemmArgs {
     int T, H, Nq, Nkv, N, L, r;
     int kx;  // length of the expand's K dimension: hidden-dimension slices of the shrink x (hi | lo) x r
     int mtiles, ntiles;
+    int kps;          // split mode: K-slices per split
+    float *partial;   // split mode: [splits][T][N] fp32
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
@@ -69,8 +72,11 @@ __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p)
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// NTW: 32-wide feature tiles per wavefront; the workgroup tile is 256 tokens x 64*NTW features
-template <int NTW>
+// NTW: 32-wide feature tiles per wavefront; the workgroup tile is 256 tokens x 64*NTW features.
+// SPLIT: small-batch mode.  blockIdx.y selects a range of K-slices; the kernel only accumulates the
+// base product over that range and stores the fp32 accumulators to g.partial[split][T][N]; adapters,
+// rounding and the q_out / cache stores are left to the finishing kernel.
+template <int NTW, bool SPLIT>
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B)
 {
     constexpr int BN = 64 * NTW;
@@ -96,8 +102,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     {
         const int t = m0 + tid;
         int a = -1;
-        if (t < g.T && g.L > 0) a = g.aeff[t];
-        slot_lds[tid] = t < g.T ? g.slot[t] : -1;
+        if (!SPLIT && t < g.T && g.L > 0) a = g.aeff[t];
+        slot_lds[tid] = (!SPLIT && t < g.T) ? g.slot[t] : -1;
         arow[tid] = a;
         if (tid < ALORA_MAX_ADAPTERS) present[tid] = 0;
         __syncthreads();
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     // ---- 2. expand first, then select ------------------------------------------------------
     bool any_adapter = false;
-    if (g.L > 0) {
+    if (!SPLIT && g.L > 0) {
         const __amdgpu_buffer_rsrc_t rs =
             make_rsrc(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
         for (int a = 0; a < g.L; ++a) {
@@ -255,13 +261,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         for (int ii = 0; ii < 8; ++ii) vx[ii] = (uint32_t)(xrow[ii] * g.H + 8 * xchunk[ii]) * 2;
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) vw[jj] = wcol_ok[jj] ? (uint32_t)(wk[jj] * g.N + 8 * wchunk[jj]) * 2 : OOR;
-        const int KT = g.H / BK;
         const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
-        issue(rx, vx, 0, rw, vw, 0, st0);
+        // K-slices of this workgroup: all of them, or the range of its split
+        const int kt0 = SPLIT ? (int)blockIdx.y * g.kps : 0;
+        const int KT = SPLIT ? min(g.H / BK, kt0 + g.kps) : g.H / BK;
+        issue(rx, vx, kt0 * xstep, rw, vw, kt0 * wstep, st0);
         // The copy of slice kt+1 is issued unconditionally inside the region that computes slice kt
         // (past the end it re-reads the last slice into the idle stage), so that the scheduler can
         // spread the copies between the MFMAs.
-        for (int kt = 0; kt < KT; kt += 2) {
+        for (int kt = kt0; kt < KT; kt += 2) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             {
@@ -289,7 +297,35 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // writes of four consecutive features, 16-byte reads along the row), so that global stores are
     // whole row segments: 64*NTW contiguous bytes of q_out or of one cache slot per token.
     __syncthreads();  // every wavefront has finished reading the K-slice stages
-    {
+    if (SPLIT) {
+        // fp32 accumulators of this split, turned around through LDS like below: 16-byte writes of
+        // four consecutive features, 16-byte reads along the row, row segments of 128*NTW bytes out
+        constexpr int EP = 128 * NTW + 16;
+        constexpr int LPR = 8 * NTW;           // lanes per row (four floats each)
+        constexpr int RPI = 64 / LPR;
+        lds_byte *strip = ((w & 2) ? st1 : st0) + (w & 1) * 32768;
+        const int er = lane / LPR, ec = lane % LPR;
+        const int n = n0 + wn * 32 * NTW + ec * 4;
+        float *out = g.partial + (size_t)blockIdx.y * g.T * g.N;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int a = 0; a < NTW; ++a)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x4 v = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1], acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
+                    *(__attribute__((address_space(3))) f32x4 *)(strip + li * EP + (a * 32 + 8 * gq + 4 * lh) * 4) = v;
+                }
+#pragma unroll
+            for (int i = 0; i < (32 + RPI - 1) / RPI; ++i) {
+                const int r = i * RPI + er;
+                const int t = m0 + wt * 128 + b * 32 + r;
+                if (er >= RPI || r >= 32 || t >= g.T || n >= g.N) continue;
+                const f32x4 v = *(const __attribute__((address_space(3))) f32x4 *)(strip + r * EP + ec * 16);
+                *(f32x4 *)(out + (size_t)t * g.N + n) = v;
+            }
+        }
+    } else {
         constexpr int EP = 64 * NTW + 16;      // strip row pitch in bytes
         constexpr int LPR = 4 * NTW;           // lanes per row (16 bytes each)
         constexpr int RPI = 64 / LPR;          // rows per store instruction
@@ -334,9 +370,69 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     }
 }
 
+// ---- host side: how a call of given sizes is tiled ---------------------------------------------
+// Everything below depends on (T, hidden, N) and on the tuning overrides only, never on adapter
+// data: a call in which every adapter id is -1 is tiled exactly like the adapted call, which is
+// what makes rows that keep the base output bit-identical between the two.
+static int g_force_ntw = 0, g_force_splits = 0;
+
+void set_gemm_tuning(int ntw, int splits)
+{
+    g_force_ntw = ntw;
+    g_force_splits = splits;
+}
+
+GemmPlan plan_gemm(int T, int H, int N)
+{
+    constexpr int CUS = 256;                       // MI355X
+    const int cand[3] = {4, 3, 2};
+    const double unit[3] = {1.0, 0.78, 0.56};      // time of one K-slice relative to the 256-wide tile
+    const int mtiles = (T + BM - 1) / BM, KT = H / BK;
+    GemmPlan best = {4, 1, KT};
+    double best_cost = 1e300;
+    for (int i = 0; i < 3; ++i) {
+        if (g_force_ntw && cand[i] != g_force_ntw) continue;
+        const long tiles = (long)mtiles * ((N + 64 * cand[i] - 1) / (64 * cand[i]));
+        // one workgroup per compute unit and round; with too few tiles to fill the chip, cut the
+        // hidden dimension into splits (each split costs an extra pass over its fp32 partials)
+        int max_splits = 1;
+        if (tiles * 2 <= CUS) max_splits = (int)std::min<long>(std::min(8, KT), CUS / tiles);
+        for (int sp = 1; sp <= max_splits; ++sp) {
+            if (g_force_splits && sp != std::min(g_force_splits, std::min(8, KT))) continue;
+            const int kps = (KT + sp - 1) / sp;
+            const int eff = (KT + kps - 1) / kps;
+            if (eff != sp) continue;
+            const long rounds = (tiles * sp + CUS - 1) / CUS;
+            const double cost = (double)rounds * (kps * unit[i] + 3.0) + (sp > 1 ? 4.0 + 0.6 * sp : 0.0);
+            if (cost < best_cost - 1e-9) { best_cost = cost; best = {cand[i], sp, kps}; }
+        }
+    }
+    return best;
+}
+
+size_t gemm_partial_bytes(int T, int H, int N)
+{
+    // room for the most splits any plan (or tuning override) can choose for these sizes
+    (void)H;
+    const long mtiles = (T + BM - 1) / BM;
+    const bool may_split = mtiles * ((N + 255) / 256) * 2 <= 256;
+    return may_split ? (size_t)8 * T * N * 4 : 0;
+}
+
+template <int NTW>
+static void launch_ntw(const GemmArgs &g, const PtrTable &B, int splits, hipStream_t stream)
+{
+    const dim3 block(GEMM_THREADS);
+    if (splits > 1)
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, true>), dim3(g.mtiles * g.ntiles, splits), block, 0, stream, g, B);
+    else
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, false>), dim3(g.mtiles * g.ntiles), block, 0, stream, g, B);
+}
+
 int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
 {
     if (f.T == 0) return 0;
+    const GemmPlan plan = plan_gemm(f.T, f.H, f.N);
     GemmArgs g;
     g.x = (const bf16_t *)f.x; g.W = (const bf16_t *)f.W; g.S_hl = (const bf16_t *)f.S;
     g.aeff = f.aeff; g.slot = f.slot;
@@ -344,31 +440,15 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
     g.T = f.T; g.H = f.H; g.Nq = f.Nq; g.Nkv = f.Nkv; g.N = f.N; g.L = f.L; g.r = f.r;
     g.kx = f.L > 0 ? shrink_slices(f.H, f.r) * 2 * f.r : 0;
     g.mtiles = (f.T + BM - 1) / BM;
-    // Feature-tile width: the one that needs the least time on `cus` compute units, counting whole
-    // rounds of one workgroup per unit (a narrower tile costs a little more per flop).  It depends
-    // on the call's sizes only, never on adapter data, so a call without adapters tiles alike.
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cus = n;
-    }
-    int best_ntw = 4;
-    double best_cost = 1e300;
-    const int cand[3] = {4, 3, 2};
-    const double unit[3] = {1.0, 0.78, 0.56};
-    for (int i = 0; i < 3; ++i) {
-        const long tiles = (long)g.mtiles * ((f.N + 64 * cand[i] - 1) / (64 * cand[i]));
-        const double cost = (double)((tiles + cus - 1) / cus) * unit[i];
-        if (cost < best_cost - 1e-9) { best_cost = cost; best_ntw = cand[i]; }
-    }
-    g.ntiles = (f.N + 64 * best_ntw - 1) / (64 * best_ntw);
-    const dim3 grid(g.mtiles * g.ntiles), block(GEMM_THREADS);
-    if (best_ntw == 4) hipLaunchKernelGGL(alora_gemm_bf16_kernel<4>, grid, block, 0, f.stream, g, B);
-    else if (best_ntw == 3) hipLaunchKernelGGL(alora_gemm_bf16_kernel<3>, grid, block, 0, f.stream, g, B);
-    else hipLaunchKernelGGL(alora_gemm_bf16_kernel<2>, grid, block, 0, f.stream, g, B);
-    return (int)hipGetLastError();
+    g.ntiles = (f.N + 64 * plan.ntw - 1) / (64 * plan.ntw);
+    g.kps = plan.kps;
+    g.partial = f.partial;
+    if (plan.ntw == 4) launch_ntw<4>(g, B, plan.splits, f.stream);
+    else if (plan.ntw == 3) launch_ntw<3>(g, B, plan.splits, f.stream);
+    else launch_ntw<2>(g, B, plan.splits, f.stream);
+    int e = (int)hipGetLastError();
+    if (e || plan.splits == 1) return e;
+    return launch_finish_bf16(f, B, plan.splits);
 }
 
 }  // namespace alora

@@ -1,32 +1,35 @@
 // Row classification (App. B mask, negated and combined with "has an adapter") and the stable
-// grouping of adapted rows by adapter id that the multi-adapter LoRA shrink walks.
+// grouping of token rows: adapted rows by adapter id (what the multi-adapter LoRA shrink and the
+// small-batch finishing kernel walk), followed by one last group of all rows that keep the base
+// output.  perm therefore is a permutation of all T rows; offsets[a] .. offsets[a+1] delimits
+// adapter a, offsets[L] .. offsets[L+1] (= T) the base group.
 //
 // One workgroup of 16 wavefronts.  A first sweep classifies every row with independent,
-// coalesced loads and parks the row's effective adapter (-1 = keeps the base output) in LDS;
-// the grouping itself then runs out of LDS.  Each wavefront owns a contiguous range of token
-// rows, so "wavefront index, then row index" is the original row order and the grouping is
-// stable without any sort: count per (wavefront, adapter), prefix-sum the counts adapter-major /
-// wavefront-minor, then place rows with wavefront-local cursors.  Ranks inside a 64-row step
-// come from ballots, so there are no data-dependent atomics and the result is deterministic.
-// Batches too large for the LDS row cache re-classify from global memory in both sweeps.
+// coalesced loads and parks the row's group key in LDS; the grouping itself then runs out of LDS.
+// Each wavefront owns a contiguous range of token rows, so "wavefront index, then row index" is
+// the original row order and the grouping is stable without any sort: count per (wavefront,
+// group), prefix-sum the counts group-major / wavefront-minor, then place rows with
+// wavefront-local cursors.  Ranks inside a 64-row step come from ballots, so there are no
+// data-dependent atomics and the result is deterministic.  Batches too large for the LDS row
+// cache re-classify from global memory in both sweeps.
 #include "alora_internal.h"
 
 namespace alora {
 
 constexpr int PREP_WAVES = 16;
 constexpr int PREP_THREADS = PREP_WAVES * 64;
-constexpr int PREP_CACHE_ROWS = 96 * 1024;  // int8 per row
+constexpr int PREP_CACHE_ROWS = 96 * 1024;     // one byte per row
+constexpr int NKEYS = ALORA_MAX_ADAPTERS + 1;  // adapters + the base group
 
 template <bool CACHED>
 __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     const int32_t *__restrict__ aid, const int32_t *__restrict__ seg, const int32_t *__restrict__ pos,
     const int32_t *__restrict__ start, int T, int L, uint8_t *__restrict__ active,
-    int8_t *__restrict__ aeff_out,
-    int32_t *__restrict__ perm, int32_t *__restrict__ offsets,
+    int8_t *__restrict__ aeff_out, int32_t *__restrict__ perm, int32_t *__restrict__ offsets,
     int4 *__restrict__ blocktab, int n_blocks)
 {
-    __shared__ int cnt[PREP_WAVES][ALORA_MAX_ADAPTERS];
-    __shared__ int goff[ALORA_MAX_ADAPTERS + 1], bfirst[ALORA_MAX_ADAPTERS + 1], tot[ALORA_MAX_ADAPTERS];
+    __shared__ int cnt[PREP_WAVES][NKEYS];
+    __shared__ int goff[3 * 64 + 1], bfirst[3 * 64 + 1], tot[3 * 64];
     __shared__ int8_t aeff[CACHED ? PREP_CACHE_ROWS : 64];
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
@@ -35,7 +38,8 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     const int t1 = min(T, t0 + per_wave);
     volatile int *my_cnt = cnt[w];
 
-    for (int i = threadIdx.x; i < PREP_WAVES * ALORA_MAX_ADAPTERS; i += PREP_THREADS) (&cnt[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < PREP_WAVES * NKEYS; i += PREP_THREADS) (&cnt[0][0])[i] = 0;
+    if (threadIdx.x < 3 * 64) tot[threadIdx.x] = 0;
     if (CACHED) {
         // classification sweep: coalesced, four independent rows per thread and trip
         for (int tb = threadIdx.x; tb < T; tb += 4 * PREP_THREADS) {
@@ -66,85 +70,94 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     }
     __syncthreads();
 
-    // pass 1: per-(wavefront, adapter) counts
-    for (int tb = t0; tb < t1; tb += 64) {
-        const int t = tb + lane;
-        int a = -1;
-        if (t < t1) {
-            if (CACHED) {
-                a = aeff[t];
-            } else {
-                a = effective_adapter(aid, seg, pos, start, t);
+    // group key of row t: its adapter if adapted, L for the base group, -1 outside the batch
+    auto row_key = [&](int t, bool publish) -> int {
+        if (t >= t1) return -1;
+        int a;
+        if (CACHED) {
+            a = aeff[t];
+        } else {
+            a = effective_adapter(aid, seg, pos, start, t);
+            if (publish) {
                 aeff_out[t] = (int8_t)a;
                 active[t] = (uint8_t)(a >= 0);
             }
         }
-        unsigned long long rem = __ballot(a >= 0);
+        return a >= 0 ? a : L;
+    };
+
+    // pass 1: per-(wavefront, group) counts
+    for (int tb = t0; tb < t1; tb += 64) {
+        const int key_l = row_key(tb + lane, true);
+        unsigned long long rem = __ballot(key_l >= 0);
         while (rem) {
             const int lead = __ffsll((long long)rem) - 1;
-            const int key = __shfl(a, lead);
-            const unsigned long long m = __ballot(a == key);
+            const int key = __shfl(key_l, lead);
+            const unsigned long long m = __ballot(key_l == key);
             if (lane == lead) my_cnt[key] = my_cnt[key] + __popcll(m);
             rem &= ~m;
         }
     }
     __syncthreads();
 
-    // exclusive prefix over wavefronts inside each adapter, adapter totals
-    if ((int)threadIdx.x < ALORA_MAX_ADAPTERS) {
+    // exclusive prefix over wavefronts inside each group, group totals
+    if ((int)threadIdx.x <= L) {
         int run = 0;
-        if ((int)threadIdx.x < L) {
-            for (int ww = 0; ww < PREP_WAVES; ++ww) {
-                const int c = cnt[ww][threadIdx.x];
-                cnt[ww][threadIdx.x] = run;
-                run += c;
-            }
+        for (int ww = 0; ww < PREP_WAVES; ++ww) {
+            const int c = cnt[ww][threadIdx.x];
+            cnt[ww][threadIdx.x] = run;
+            run += c;
         }
         tot[threadIdx.x] = run;
     }
     __syncthreads();
-    // one wavefront scans the adapter totals (two adapters per lane): row offsets of the groups
-    // and first 32-row block of every adapter in the shrink's block table
+    // one wavefront scans the group totals (three groups per lane): row offsets of the groups and
+    // first 32-row block of every group in the block table
     if (w == 0) {
-        const int c0 = tot[2 * lane], c1 = tot[2 * lane + 1];
-        const int b0 = (c0 + 31) >> 5, b1 = (c1 + 31) >> 5;
-        int rows = c0 + c1, blks = b0 + b1;
+        int c[3], b[3], rows = 0, blks = 0;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            c[u] = tot[3 * lane + u];
+            b[u] = (c[u] + 31) >> 5;
+            rows += c[u];
+            blks += b[u];
+        }
+        const int my_rows = rows, my_blks = blks;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
             const int r_up = __shfl_up(rows, d), b_up = __shfl_up(blks, d);
             if (lane >= d) { rows += r_up; blks += b_up; }
         }
-        goff[2 * lane] = rows - c0 - c1;
-        goff[2 * lane + 1] = rows - c1;
-        bfirst[2 * lane] = blks - b0 - b1;
-        bfirst[2 * lane + 1] = blks - b1;
-        if (lane == 63) { goff[ALORA_MAX_ADAPTERS] = rows; bfirst[ALORA_MAX_ADAPTERS] = blks; }
+        int ro = rows - my_rows, bo = blks - my_blks;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            goff[3 * lane + u] = ro;
+            bfirst[3 * lane + u] = bo;
+            ro += c[u];
+            bo += b[u];
+        }
+        if (lane == 63) { goff[3 * 64] = rows; bfirst[3 * 64] = blks; }
     }
     __syncthreads();
-    if ((int)threadIdx.x <= L) offsets[threadIdx.x] = goff[threadIdx.x];
-    // block table: entry b = (adapter, first index into perm, rows in block, 0); unused entries -1
-    if ((int)threadIdx.x < L) {
+    if ((int)threadIdx.x <= L + 1) offsets[threadIdx.x] = goff[threadIdx.x];
+    // block table: entry = (group, first index into perm, rows in block, 0); unused entries -1
+    if ((int)threadIdx.x <= L) {
         const int a = threadIdx.x, n = tot[a], o = goff[a];
-        for (int b = 0; b * 32 < n; ++b) {
-            int4 e = make_int4(a, o + 32 * b, min(32, n - 32 * b), 0);
-            blocktab[bfirst[a] + b] = e;
-        }
+        for (int b = 0; b * 32 < n; ++b) blocktab[bfirst[a] + b] = make_int4(a, o + 32 * b, min(32, n - 32 * b), 0);
     }
-    for (int b = bfirst[ALORA_MAX_ADAPTERS] + threadIdx.x; b < n_blocks; b += PREP_THREADS)
-        blocktab[b] = make_int4(-1, 0, 0, 0);
+    for (int b = bfirst[3 * 64] + threadIdx.x; b < n_blocks; b += PREP_THREADS) blocktab[b] = make_int4(-1, 0, 0, 0);
 
     // pass 2: placement
     for (int tb = t0; tb < t1; tb += 64) {
         const int t = tb + lane;
-        int a = -1;
-        if (t < t1) a = CACHED ? (int)aeff[t] : effective_adapter(aid, seg, pos, start, t);
-        unsigned long long rem = __ballot(a >= 0);
+        const int key_l = row_key(t, false);
+        unsigned long long rem = __ballot(key_l >= 0);
         while (rem) {
             const int lead = __ffsll((long long)rem) - 1;
-            const int key = __shfl(a, lead);
-            const unsigned long long m = __ballot(a == key);
+            const int key = __shfl(key_l, lead);
+            const unsigned long long m = __ballot(key_l == key);
             const int base = goff[key] + my_cnt[key];
-            if (a == key) {
+            if (key_l == key) {
                 const unsigned long long below = m & ((1ull << lane) - 1ull);
                 perm[base + __popcll(below)] = t;
             }
@@ -155,6 +168,8 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
         }
     }
 }
+
+int group_blocks(int T, int L) { return (T + 31) / 32 + L + 1; }
 
 int launch_classify_group(const Fwd &f)
 {

@@ -43,13 +43,12 @@ static inline int shrink_slice_len(int H, int r)
     const int chunks = (H + c - 1) / c, ks = shrink_slices(H, r);
     return ((chunks + ks - 1) / ks) * c;
 }
-int shrink_blocks(int T, int L) { return (T + 31) / 32 + L; }
 
 // KSL: chunk length; NT: 32-wide rank tiles (1 for rank <= 32, else 2)
 template <int KSL, int NT>
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restrict__ x, PtrTable A,
                                                           const int32_t *__restrict__ perm,
-                                                          const int4 *__restrict__ blocktab, int H, int r,
+                                                          const int4 *__restrict__ blocktab, int L, int H, int r,
                                                           int slice_len, bf16_t *__restrict__ S_hl)
 {
     constexpr int XROW_BYTES = KSL * 2;
@@ -64,7 +63,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
     // which (adapter, 32-row block) is this workgroup?  (table written by the grouping kernel)
     const int4 entry = blocktab[blockIdx.y];
     const int a = entry.x, j0 = entry.y, cnt = entry.z;
-    if (a < 0) return;  // uniform across the workgroup
+    if (a < 0 || a >= L) return;  // unused entry or the base group; uniform across the workgroup
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -167,14 +166,14 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;
-    const dim3 grid(shrink_slices(f.H, f.r), shrink_blocks(f.T, f.L));
+    const dim3 grid(shrink_slices(f.H, f.r), f.n_blocks);
     const int sl = shrink_slice_len(f.H, f.r);
     if (f.r <= 32)
         hipLaunchKernelGGL((shrink_bf16_kernel<1024, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
-                           f.blocktab, f.H, f.r, sl, (bf16_t *)f.S);
+                           f.blocktab, f.L, f.H, f.r, sl, (bf16_t *)f.S);
     else
         hipLaunchKernelGGL((shrink_bf16_kernel<512, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
-                           f.blocktab, f.H, f.r, sl, (bf16_t *)f.S);
+                           f.blocktab, f.L, f.H, f.r, sl, (bf16_t *)f.S);
     return (int)hipGetLastError();
 }
 

@@ -92,3 +92,15 @@ def maxnorm_rel(got: np.ndarray, ref: np.ndarray) -> float:
     if denom == 0:
         denom = 1.0
     return float(np.max(np.abs(got - ref)) / denom) if ref.size else 0.0
+
+
+def check_grouping(act_g, perm_g, off_g, ref_active, ref_perm, ref_offsets) -> None:
+    """Integer results of the classification/grouping step against the oracle, bit for bit:
+    flags, adapter groups in stable order, and the trailing group of rows that keep the base output."""
+    act_g, perm_g, off_g = act_g.cpu().numpy(), perm_g.cpu().numpy(), off_g.cpu().numpy()
+    T, L = ref_active.shape[0], ref_offsets.shape[0] - 1
+    assert np.array_equal(act_g, ref_active)
+    assert np.array_equal(off_g[: L + 1], ref_offsets)
+    assert off_g[L + 1] == T
+    assert np.array_equal(perm_g[: ref_perm.size], ref_perm)
+    assert np.array_equal(perm_g[ref_perm.size: T], np.nonzero(ref_active == 0)[0])

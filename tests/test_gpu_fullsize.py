@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2512_17910_amd import binding as ab
 from paper_2512_17910_amd import workloads as wl
-from gpu_util import DeviceBatch, TOL, host_operands, maxnorm_rel, to_f64
+from gpu_util import DeviceBatch, TOL, check_grouping, host_operands, maxnorm_rel, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -29,10 +29,7 @@ def test_full_size_config(cfg, n_sample):
     # integer results, exact
     mask, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
     perm, off = oracle.group(w.token_adapter_ids, act, w.n_adapters)
-    a_g, p_g, o_g = ab.workspace_int_views(db.dims, db.ws)
-    assert np.array_equal(a_g.cpu().numpy(), act)
-    assert np.array_equal(o_g.cpu().numpy(), off)
-    assert np.array_equal(p_g.cpu().numpy()[: perm.size], perm)
+    check_grouping(*ab.workspace_int_views(db.dims, db.ws), act, perm, off)
 
     # sampled rows against the oracle
     rows = wl.sample_rows(w, n_sample)

@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2512_17910_amd import binding as ab
 from paper_2512_17910_amd import workloads as wl
-from gpu_util import DeviceBatch, TOL, host_operands, maxnorm_rel, raw_bits, to_f64
+from gpu_util import DeviceBatch, TOL, check_grouping, host_operands, maxnorm_rel, raw_bits, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -45,10 +45,7 @@ def _check_full(w, db=None, elementwise=True):
     assert np.array_equal(raw_bits(db.kc)[un], raw_bits(db.k0)[un])
     assert np.array_equal(raw_bits(db.vc)[un], raw_bits(db.v0)[un])
     # integer results left in the workspace
-    act, perm, off = ab.workspace_int_views(db.dims, db.ws)
-    assert np.array_equal(act.cpu().numpy(), ref.active)
-    assert np.array_equal(off.cpu().numpy(), ref.offsets)
-    assert np.array_equal(perm.cpu().numpy()[: ref.perm.size], ref.perm)
+    check_grouping(*ab.workspace_int_views(db.dims, db.ws), ref.active, ref.perm, ref.offsets)
     return db, ref
 
 
@@ -71,6 +68,32 @@ SMALL = [
 @pytest.mark.parametrize("kw", SMALL, ids=[f"{k['dtype']}-{k['seed']}" for k in SMALL])
 def test_small_mixed(kw):
     _check_full(wl.small_mixed(**kw))
+
+
+@pytest.fixture
+def tuning():
+    """Force a tiling of the bf16 path for one test, restore the automatic choice afterwards."""
+    yield ab.alora_qkv_set_tuning
+    ab.alora_qkv_set_tuning(0, 0)
+
+
+# (feature tiles, splits): every kernel variant, fused and split, on multi-tile ragged batches
+TILINGS = [(4, 1), (3, 1), (2, 1), (4, 2), (3, 4), (2, 3), (0, 0)]
+
+
+@pytest.mark.parametrize("ft,sp", TILINGS, ids=[f"tiles{a}-splits{b}" for a, b in TILINGS])
+def test_every_tiling_matches_the_oracle(tuning, ft, sp):
+    tuning(ft, sp)
+    _check_full(wl.small_mixed("bf16", seed=2, seq_lens=(300, 41, 1, 77, 256, 3), pad_every=17))
+    _check_full(wl.small_mixed("bf16", seed=5, rank=24, n_adapters=5, hidden=320, n_q_heads=9, head_dim=32,
+                               seq_lens=(513, 5)))
+    _check_full(wl.small_mixed("bf16", seed=4, rank=64, n_adapters=2, hidden=128, seq_lens=(33, 64, 31)))
+
+
+@pytest.mark.parametrize("ft,sp", [(4, 1), (2, 4)], ids=["fused", "split"])
+def test_pre_activation_bit_identity_in_both_paths(tuning, ft, sp):
+    tuning(ft, sp)
+    test_pre_activation_rows_bit_identical_to_base_run("bf16")
 
 
 def test_decode_like_many_adapters():
@@ -180,9 +203,7 @@ def test_classify_group_large_random():
         ws = ab.alloc_workspace(dims)
         a_g, p_g, o_g = ab.alora_qkv_classify_group(d[0], d[3], dims, ws)
         torch.cuda.synchronize()
-        assert np.array_equal(a_g.cpu().numpy(), act)
-        assert np.array_equal(o_g.cpu().numpy(), off)
-        assert np.array_equal(p_g.cpu().numpy()[: perm.size], perm)
+        check_grouping(a_g, p_g, o_g, act, perm, off)
 
 
 def test_validate_reports_bad_data():
