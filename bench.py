@@ -38,6 +38,9 @@ def main() -> int:
                     help="distinct copies of W/A/B cycled through (0 = 8 for the decode config, else 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (known size) so that a rocprofv3 --pmc run of this "
+                         "command holds a reference dispatch for the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -63,6 +66,13 @@ def main() -> int:
         ab.alora_qkv_forward(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot,
                              w.block_size, db.dims, db.ws)
 
+    if args.calibrate_copy:
+        src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -84,8 +94,13 @@ def main() -> int:
     T_w = int((w.slot_mapping >= 0).sum())
     e = w.elem_bytes
     flops = 2.0 * w.T * w.hidden * w.N + 2.0 * T_act * w.rank * w.N
-    bytes_ = e * (w.T * w.hidden + w.hidden * w.N + used * w.rank * w.N + T_act * 2 * w.rank
-                  + w.T * w.Nq + T_w * 2 * w.Nkv) + w.T * (4 + 4 + 4 + 8) + 4 * w.n_segments
+    if args.config == 3:
+        # small-batch path: the dominant kernel is the split projection, which streams x and W;
+        # adapters, rounding and the stores belong to the finishing kernel
+        bytes_ = e * (w.T * w.hidden + w.hidden * w.N)
+    else:
+        bytes_ = e * (w.T * w.hidden + w.hidden * w.N + used * w.rank * w.N + T_act * 2 * w.rank
+                      + w.T * w.Nq + T_w * 2 * w.Nkv) + w.T * (1 + 8)
     bound = BOUND[args.config]
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -39,6 +39,8 @@ static int check_dims(const alora_dims *d)
         if (d->n_adapters > 0 && d->rank % 8) return ALORA_ESHAPE;
         // 32-bit byte offsets inside the weight matrix (buffer addressing)
         if ((long long)d->hidden * (Nq + 2 * Nkv) * 2 >= (1ll << 31)) return ALORA_ESHAPE;
+        // 32-bit byte offsets of the gathered token rows in the shrink
+        if (d->n_adapters > 0 && (long long)d->T * d->hidden * 2 > 0xfffffff0ll) return ALORA_ESHAPE;
     } else {
         if (d->hidden % 4 || Nq % 4 || Nkv % 4) return ALORA_ESHAPE;
     }
@@ -54,8 +56,8 @@ static Layout make_layout(const alora_dims *d)
     l.aeff = o;    o += up256(T);
     l.perm = o;    o += up256(4 * T);
     l.offsets = o; o += up256(4 * (L + 2));
-    // f32: [T,r] fp32; bf16: [T, slices, 2r] bf16 (hi | lo halves of every hidden-dimension slice)
-    l.S = o;       o += up256(d->dtype == ALORA_BF16 ? T * r * 4 * (size_t)shrink_slices(d->hidden, d->rank ? d->rank : 8) : T * r * 4);
+    // f32: [T,r] fp32; bf16: [T,2r] bf16 (hi | lo halves of the fp32 shrink result)
+    l.S = o;       o += up256(T * r * 4);
     l.n_blocks = group_blocks(d->T, d->n_adapters);
     l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
     l.partial = o;
@@ -200,15 +202,15 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
             e = launch_shrink_f32(f, ta);
             if (!e && timed) e = (int)hipEventRecord(g_prof.ev0[g_prof.used], f.stream);
             if (!e) e = launch_gemm_f32(f, tb);
+            if (!e && timed) e = (int)hipEventRecord(g_prof.ev1[g_prof.used], f.stream);
         } else {
             e = launch_shrink_bf16(f, ta);
             if (!e && timed) e = (int)hipEventRecord(g_prof.ev0[g_prof.used], f.stream);
-            if (!e) e = launch_gemm_bf16(f, tb);
+            // the second event is recorded right behind the projection kernel (before the finishing
+            // kernel of the small-batch path)
+            if (!e) e = launch_gemm_bf16(f, tb, timed ? g_prof.ev1[g_prof.used] : nullptr);
         }
-        if (!e && timed) {
-            e = (int)hipEventRecord(g_prof.ev1[g_prof.used], f.stream);
-            g_prof.used++;
-        }
+        if (!e && timed) g_prof.used++;
     }
     if (e) { g_last_hip_error = e; return ALORA_EHIP; }
     return ALORA_OK;

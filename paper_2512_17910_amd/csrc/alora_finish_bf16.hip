@@ -8,7 +8,11 @@
 // rounds once to bf16 and stores q_out / the paged K and V slots.  Rows of the base group never
 // touch S or B, and their arithmetic does not depend on which rows are adapted: they come out
 // bit-identical to a call without adapters.  The low-rank term is plain fp32 FMAs (rank x 8 per
-// thread and row), S rebuilt from the (hi, lo) bf16 pairs the shrink stored per hidden slice.
+// thread), S rebuilt from the (hi, lo) bf16 pair the shrink stored.
+//
+// One thread per (row, 8 features): 1024 threads.  The kernel is a chain of dependent loads
+// (table entry -> row ids -> data), so everything after the row ids is issued at once: all
+// splits' partials, the S row and the B slice.
 #include "alora_internal.h"
 
 namespace alora {
@@ -18,18 +22,17 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int FIN_COLS = 256;  // features per workgroup: 32 threads x 8 features per row
 
-__global__ __launch_bounds__(256) void finish_bf16_kernel(const float *__restrict__ partial, int splits,
-                                                          const bf16_t *__restrict__ S_hl, int kslices, PtrTable B,
-                                                          const int32_t *__restrict__ perm,
-                                                          const int4 *__restrict__ blocktab,
-                                                          const int64_t *__restrict__ slot, bf16_t *__restrict__ q,
-                                                          bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int T, int Nq,
-                                                          int Nkv, int L, int r)
+template <int SPLITS>
+__global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restrict__ partial,
+                                                           const bf16_t *__restrict__ S_hl, PtrTable B,
+                                                           const int32_t *__restrict__ perm,
+                                                           const int4 *__restrict__ blocktab,
+                                                           const int64_t *__restrict__ slot, bf16_t *__restrict__ q,
+                                                           bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int T, int Nq,
+                                                           int Nkv, int L, int r)
 {
     __shared__ float s_lds[32][ALORA_MAX_RANK + 1];
     __shared__ __attribute__((aligned(16))) bf16_t b_lds[ALORA_MAX_RANK][FIN_COLS];
-    __shared__ int rows_t[32];
-    __shared__ int64_t rows_slot[32];
 
     const int4 entry = blocktab[blockIdx.x];
     const int a = entry.x, j0 = entry.y, cnt = entry.z;
@@ -38,93 +41,100 @@ __global__ __launch_bounds__(256) void finish_bf16_kernel(const float *__restric
     const int n0 = blockIdx.y * FIN_COLS;
     const int tid = threadIdx.x;
     const bool adapted = a < L;
+    const int i = tid >> 5, c = tid & 31, n = n0 + 8 * c;
+    const bool live = i < cnt && n < N;
+    const int t = i < cnt ? perm[j0 + i] : -1;
 
-    if (tid < 32) {
-        const int t = tid < cnt ? perm[j0 + tid] : -1;
-        rows_t[tid] = t;
-        rows_slot[tid] = t >= 0 ? slot[t] : -1;
-    }
-    __syncthreads();
-    if (adapted) {
-        // S rows of the block: sum of the slices' (hi + lo), slice order
-        for (int idx = tid; idx < 32 * r; idx += 256) {
-            const int i = idx / r, j = idx % r;
-            const int t = rows_t[i];
-            float s = 0.f;
-            if (t >= 0) {
-                const bf16_t *row = S_hl + (size_t)t * kslices * 2 * r;
-                for (int sl = 0; sl < kslices; ++sl)
-                    s += bf16_bits_to_f32(row[sl * 2 * r + j]) + bf16_bits_to_f32(row[sl * 2 * r + r + j]);
-            }
-            s_lds[i][j] = s;
+    // everything that depends on the row id, issued together
+    f32x4 plo[SPLITS], phi[SPLITS];
+    int64_t sl = -1;
+    if (live) {
+#pragma unroll
+        for (int s = 0; s < SPLITS; ++s) {
+            const float *p = partial + ((size_t)s * T + t) * N + n;
+            plo[s] = *(const f32x4 *)p;
+            phi[s] = *(const f32x4 *)(p + 4);
         }
-        // B[a][:, n0 : n0+256]
+        if (n >= Nq) sl = slot[t];
+    }
+    if (adapted) {
+        // S of row i, rank columns c, c+32: hi + lo
+        if (t >= 0) {
+            const bf16_t *row = S_hl + (size_t)t * 2 * r;
+            for (int j = c; j < r; j += 32) s_lds[i][j] = bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j]);
+        }
+        // B[a][:, n0 : n0+256]: rank rows x 32 chunks of 8 features
         const bf16_t *Ba = (const bf16_t *)B.p[a];
-        for (int idx = tid; idx < r * (FIN_COLS / 8); idx += 256) {
-            const int j = idx / (FIN_COLS / 8), c = idx % (FIN_COLS / 8);
+        for (int idx = tid; idx < r * (FIN_COLS / 8); idx += 1024) {
+            const int j = idx / (FIN_COLS / 8), cc = idx % (FIN_COLS / 8);
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (n0 + 8 * c < N) v = *(const u32x4 *)(Ba + (size_t)j * N + n0 + 8 * c);
-            *(u32x4 *)&b_lds[j][8 * c] = v;
+            if (n0 + 8 * cc < N) v = *(const u32x4 *)(Ba + (size_t)j * N + n0 + 8 * cc);
+            *(u32x4 *)&b_lds[j][8 * cc] = v;
         }
         __syncthreads();
     }
+    if (!live) return;
 
-    const int c = tid & 31, n = n0 + 8 * c;
-    if (n >= N) return;
-    int region, col;
-    if (n < Nq) { region = 0; col = n; }
-    else if (n < Nq + Nkv) { region = 1; col = n - Nq; }
-    else { region = 2; col = n - Nq - Nkv; }
-
-    for (int i = tid >> 5; i < cnt; i += 8) {
-        const int t = rows_t[i];
-        float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < splits; ++s) {
-            const float *p = partial + ((size_t)s * T + t) * N + n;
-            const f32x4 lo = *(const f32x4 *)p, hi = *(const f32x4 *)(p + 4);
-            y[0] += lo.x; y[1] += lo.y; y[2] += lo.z; y[3] += lo.w;
-            y[4] += hi.x; y[5] += hi.y; y[6] += hi.z; y[7] += hi.w;
-        }
-        if (adapted) {
-            float d[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            for (int j = 0; j < r; ++j) {
-                const float sj = s_lds[i][j];
-                const u32x4 bv = *(const u32x4 *)&b_lds[j][8 * c];
-                d[0] = fmaf(sj, __uint_as_float(bv.x << 16), d[0]);
-                d[1] = fmaf(sj, __uint_as_float(bv.x & 0xffff0000u), d[1]);
-                d[2] = fmaf(sj, __uint_as_float(bv.y << 16), d[2]);
-                d[3] = fmaf(sj, __uint_as_float(bv.y & 0xffff0000u), d[3]);
-                d[4] = fmaf(sj, __uint_as_float(bv.z << 16), d[4]);
-                d[5] = fmaf(sj, __uint_as_float(bv.z & 0xffff0000u), d[5]);
-                d[6] = fmaf(sj, __uint_as_float(bv.w << 16), d[6]);
-                d[7] = fmaf(sj, __uint_as_float(bv.w & 0xffff0000u), d[7]);
-            }
+    float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] += d[e];
-        }
-        u32x4 out;
-        {
-            const f32x2 p0 = {y[0], y[1]}, p1 = {y[2], y[3]}, p2 = {y[4], y[5]}, p3 = {y[6], y[7]};
-            out.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2));
-            out.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2));
-            out.z = __builtin_bit_cast(uint32_t, __builtin_convertvector(p2, bf16x2));
-            out.w = __builtin_bit_cast(uint32_t, __builtin_convertvector(p3, bf16x2));
-        }
-        if (region == 0) {
-            *(u32x4 *)(q + (size_t)t * Nq + col) = out;
-        } else {
-            const int64_t sl = rows_slot[i];
-            if (sl >= 0) *(u32x4 *)((region == 1 ? kc : vc) + (size_t)sl * Nkv + col) = out;
-        }
+    for (int s = 0; s < SPLITS; ++s) {
+        y[0] += plo[s].x; y[1] += plo[s].y; y[2] += plo[s].z; y[3] += plo[s].w;
+        y[4] += phi[s].x; y[5] += phi[s].y; y[6] += phi[s].z; y[7] += phi[s].w;
     }
+    if (adapted) {
+        float d[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < r; ++j) {
+            const float sj = s_lds[i][j];
+            const u32x4 bv = *(const u32x4 *)&b_lds[j][8 * c];
+            d[0] = fmaf(sj, __uint_as_float(bv.x << 16), d[0]);
+            d[1] = fmaf(sj, __uint_as_float(bv.x & 0xffff0000u), d[1]);
+            d[2] = fmaf(sj, __uint_as_float(bv.y << 16), d[2]);
+            d[3] = fmaf(sj, __uint_as_float(bv.y & 0xffff0000u), d[3]);
+            d[4] = fmaf(sj, __uint_as_float(bv.z << 16), d[4]);
+            d[5] = fmaf(sj, __uint_as_float(bv.z & 0xffff0000u), d[5]);
+            d[6] = fmaf(sj, __uint_as_float(bv.w << 16), d[6]);
+            d[7] = fmaf(sj, __uint_as_float(bv.w & 0xffff0000u), d[7]);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[e] += d[e];
+    }
+    u32x4 out;
+    {
+        const f32x2 p0 = {y[0], y[1]}, p1 = {y[2], y[3]}, p2 = {y[4], y[5]}, p3 = {y[6], y[7]};
+        out.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2));
+        out.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2));
+        out.z = __builtin_bit_cast(uint32_t, __builtin_convertvector(p2, bf16x2));
+        out.w = __builtin_bit_cast(uint32_t, __builtin_convertvector(p3, bf16x2));
+    }
+    if (n < Nq) {
+        *(u32x4 *)(q + (size_t)t * Nq + n) = out;
+    } else if (sl >= 0) {
+        if (n < Nq + Nkv) *(u32x4 *)(kc + (size_t)sl * Nkv + (n - Nq)) = out;
+        else *(u32x4 *)(vc + (size_t)sl * Nkv + (n - Nq - Nkv)) = out;
+    }
+}
+
+template <int SPLITS>
+static void launch_finish(const Fwd &f, const PtrTable &B)
+{
+    const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
+    hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
+                       (const bf16_t *)f.S, B, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
+                       (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
 }
 
 int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits)
 {
-    const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
-    hipLaunchKernelGGL(finish_bf16_kernel, grid, dim3(256), 0, f.stream, (const float *)f.partial, splits,
-                       (const bf16_t *)f.S, f.L > 0 ? shrink_slices(f.H, f.r) : 0, B, f.perm, f.blocktab, f.slot,
-                       (bf16_t *)f.q, (bf16_t *)f.kc, (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
+    switch (splits) {
+    case 2: launch_finish<2>(f, B); break;
+    case 3: launch_finish<3>(f, B); break;
+    case 4: launch_finish<4>(f, B); break;
+    case 5: launch_finish<5>(f, B); break;
+    case 6: launch_finish<6>(f, B); break;
+    case 7: launch_finish<7>(f, B); break;
+    case 8: launch_finish<8>(f, B); break;
+    default: return (int)hipErrorInvalidValue;
+    }
     return (int)hipGetLastError();
 }
 

@@ -3,8 +3,8 @@
 //
 // Per 256(token) x 256|192|128(feature) tile, one workgroup of four wavefronts (one per SIMD):
 //   1. classify the tile's rows (App. B mask); list the adapters its adapted rows use
-//   2. expand first: for each such adapter a, accumulate [S_hi | S_lo | ...](rows of a, else 0) . [B_a ; B_a ; ...]
-//      (one hi/lo pair per hidden-dimension slice of the shrink) as extra K-slices of the same MFMA loop, then zero the accumulators of rows that are not
+//   2. expand first: for each such adapter a, accumulate [S_hi | S_lo](rows of a, else 0) . [B_a ; B_a]
+//      as extra K-slices of the same MFMA loop, then zero the accumulators of rows that are not
 //      adapted (a select, not a multiply: adapter data never reaches a base row)
 //   3. base GEMM over the hidden dimension: rows that are not adapted see exactly the
 //      instruction sequence of a call without adapters, so they come out bit-identical to it
@@ -45,7 +45,7 @@ struct GemmArgs {
     const int64_t *slot;
     bf16_t *q, *kc, *vc;
     int T, H, Nq, Nkv, N, L, r;
-    int kx;  // length of the expand's K dimension: hidden-dimension slices of the shrink x (hi | lo) x r
+    int kx;  // length of the expand K dimension: (hi | lo) x r
     int mtiles, ntiles;
     int kps;          // split mode: K-slices per split
     float *partial;   // split mode: [splits][T][N] fp32
@@ -92,7 +92,20 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int mt = blockIdx.x % g.mtiles, nt = blockIdx.x / g.mtiles;
+    // Tile of this workgroup.  Workgroups are handed to the 8 XCDs round-robin, and each XCD has its
+    // own L2: XCD k = blockIdx.x % 8 takes a contiguous range of a tile order that walks panels of
+    // 4 token tiles, feature tile by feature tile, so that the ~32 tiles an XCD runs at a time form
+    // a 4 x 8 patch sharing their token and weight slices in that L2.
+    int mt, nt;
+    {
+        const int total = g.mtiles * g.ntiles, chunk = (total + 7) >> 3;
+        const int l = ((int)blockIdx.x & 7) * chunk + ((int)blockIdx.x >> 3);
+        if (l >= total) return;  // grid is padded to a multiple of 8; uniform across the workgroup
+        const int panel = l / (4 * g.ntiles), rem = l - panel * 4 * g.ntiles;
+        const int pm = min(4, g.mtiles - 4 * panel);
+        nt = rem / pm;
+        mt = 4 * panel + rem - nt * pm;
+    }
     const int m0 = mt * BM, n0 = nt * BN;
     const int wt = w & 1, wn = w >> 1;   // wave owns tokens [wt*128,+128) x features [wn*32*NTW,+32*NTW)
     const int li = lane & 31, lh = lane >> 5;
@@ -423,13 +436,14 @@ template <int NTW>
 static void launch_ntw(const GemmArgs &g, const PtrTable &B, int splits, hipStream_t stream)
 {
     const dim3 block(GEMM_THREADS);
+    const int tiles8 = (g.mtiles * g.ntiles + 7) / 8 * 8;  // see the tile order in the kernel
     if (splits > 1)
-        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, true>), dim3(g.mtiles * g.ntiles, splits), block, 0, stream, g, B);
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, true>), dim3(tiles8, splits), block, 0, stream, g, B);
     else
-        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, false>), dim3(g.mtiles * g.ntiles), block, 0, stream, g, B);
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, false>), dim3(tiles8), block, 0, stream, g, B);
 }
 
-int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
+int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projection)
 {
     if (f.T == 0) return 0;
     const GemmPlan plan = plan_gemm(f.T, f.H, f.N);
@@ -438,7 +452,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
     g.aeff = f.aeff; g.slot = f.slot;
     g.q = (bf16_t *)f.q; g.kc = (bf16_t *)f.kc; g.vc = (bf16_t *)f.vc;
     g.T = f.T; g.H = f.H; g.Nq = f.Nq; g.Nkv = f.Nkv; g.N = f.N; g.L = f.L; g.r = f.r;
-    g.kx = f.L > 0 ? shrink_slices(f.H, f.r) * 2 * f.r : 0;
+    g.kx = 2 * f.r;
     g.mtiles = (f.T + BM - 1) / BM;
     g.ntiles = (f.N + 64 * plan.ntw - 1) / (64 * plan.ntw);
     g.kps = plan.kps;
@@ -447,6 +461,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B)
     else if (plan.ntw == 3) launch_ntw<3>(g, B, plan.splits, f.stream);
     else launch_ntw<2>(g, B, plan.splits, f.stream);
     int e = (int)hipGetLastError();
+    if (!e && after_projection) e = (int)hipEventRecord(after_projection, f.stream);
     if (e || plan.splits == 1) return e;
     return launch_finish_bf16(f, B, plan.splits);
 }

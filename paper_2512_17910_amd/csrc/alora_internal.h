@@ -32,7 +32,7 @@ struct Fwd {
     uint8_t *active;
     int8_t *aeff;        // [T] adapter id of adapted rows, -1 for rows that keep the base output
     int32_t *perm, *offsets;
-    void *S;          // bf16: [T, slices, 2r] bf16 (hi | lo halves per hidden-dimension slice); f32: [T,r] fp32
+    void *S;          // bf16: [T,2r] bf16 (hi | lo halves of the fp32 shrink result); f32: [T,r] fp32
     float *partial;      // small-batch path: fp32 partial products [splits][T][N]
     int4 *blocktab;      // shrink: (adapter, first perm index, rows, 0) per 32-row block; adapter -1 = unused
     int n_blocks;        // entries in blocktab (upper bound on 32-row blocks)
@@ -64,7 +64,7 @@ int launch_classify_group(const Fwd &f);
 int launch_shrink_f32(const Fwd &f, const PtrTable &A);
 int launch_gemm_f32(const Fwd &f, const PtrTable &B);
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A);
-int launch_gemm_bf16(const Fwd &f, const PtrTable &B);
+int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projection);
 int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits);
 struct GemmPlan {
     int ntw;     // 32-wide feature tiles per wavefront (tile width 64 * ntw)
@@ -75,6 +75,5 @@ GemmPlan plan_gemm(int T, int H, int N);
 size_t gemm_partial_bytes(int T, int H, int N);
 void set_gemm_tuning(int ntw, int splits);
 int group_blocks(int T, int L);
-int shrink_slices(int H, int r);
 
 }  // namespace alora

@@ -36,31 +36,36 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     const int per_wave = ((T + PREP_WAVES * 64 - 1) / (PREP_WAVES * 64)) * 64;
     const int t0 = min(T, w * per_wave);
     const int t1 = min(T, t0 + per_wave);
-    volatile int *my_cnt = cnt[w];
+    int *my_cnt = cnt[w];  // plain LDS accesses: a volatile one would wait for every outstanding global store
 
     for (int i = threadIdx.x; i < PREP_WAVES * NKEYS; i += PREP_THREADS) (&cnt[0][0])[i] = 0;
     if (threadIdx.x < 3 * 64) tot[threadIdx.x] = 0;
     if (CACHED) {
-        // classification sweep: coalesced, four independent rows per thread and trip
-        for (int tb = threadIdx.x; tb < T; tb += 4 * PREP_THREADS) {
-            int a[4];
+        // classification sweep: coalesced, sixteen independent rows per thread and trip, so that a
+        // batch of 16K rows pays the three dependent load latencies (adapter id -> segment and
+        // position -> activation start) once
+        constexpr int U = 16;
+        for (int tb = threadIdx.x; tb < T; tb += U * PREP_THREADS) {
+            int a[U], s[U], p[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int t = tb + u * PREP_THREADS;
                 a[u] = t < T ? aid[t] : -1;
             }
-            int s[4], p[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int t = tb + u * PREP_THREADS;
                 s[u] = a[u] >= 0 ? seg[t] : 0;
                 p[u] = a[u] >= 0 ? pos[t] : 0;
             }
+            int st[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < U; ++u) st[u] = a[u] >= 0 ? start[s[u]] : 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
                 const int t = tb + u * PREP_THREADS;
                 if (t < T) {
-                    const int e = (a[u] >= 0 && p[u] >= start[s[u]]) ? a[u] : -1;
+                    const int e = (a[u] >= 0 && p[u] >= st[u]) ? a[u] : -1;
                     aeff[t] = (int8_t)e;
                     aeff_out[t] = (int8_t)e;
                     active[t] = (uint8_t)(e >= 0);
@@ -86,17 +91,26 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
         return a >= 0 ? a : L;
     };
 
+    const int key_bits = 32 - __clz(L | 1);  // keys are 0 .. L
+    // lanes of this 64-row step that hold the same key as this lane (one ballot per key bit: the
+    // cost does not grow with the number of distinct groups in the step, as in a decode batch)
+    auto same_key_lanes = [&](int key_l) -> unsigned long long {
+        unsigned long long same = __ballot(key_l >= 0);
+        for (int bit = 0; bit < key_bits; ++bit) {
+            const bool mine = (key_l >> bit) & 1;
+            const unsigned long long b = __ballot(mine);
+            same &= mine ? b : ~b;
+        }
+        return key_l >= 0 ? same : 0ull;
+    };
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+
     // pass 1: per-(wavefront, group) counts
     for (int tb = t0; tb < t1; tb += 64) {
         const int key_l = row_key(tb + lane, true);
-        unsigned long long rem = __ballot(key_l >= 0);
-        while (rem) {
-            const int lead = __ffsll((long long)rem) - 1;
-            const int key = __shfl(key_l, lead);
-            const unsigned long long m = __ballot(key_l == key);
-            if (lane == lead) my_cnt[key] = my_cnt[key] + __popcll(m);
-            rem &= ~m;
-        }
+        const unsigned long long same = same_key_lanes(key_l);
+        if (same && !(same & lanes_below)) atomicAdd(&my_cnt[key_l], __popcll(same));
+        __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
 
@@ -141,31 +155,30 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     __syncthreads();
     if ((int)threadIdx.x <= L + 1) offsets[threadIdx.x] = goff[threadIdx.x];
     // block table: entry = (group, first index into perm, rows in block, 0); unused entries -1
-    if ((int)threadIdx.x <= L) {
-        const int a = threadIdx.x, n = tot[a], o = goff[a];
-        for (int b = 0; b * 32 < n; ++b) blocktab[bfirst[a] + b] = make_int4(a, o + 32 * b, min(32, n - 32 * b), 0);
+    for (int e = threadIdx.x; e < n_blocks; e += PREP_THREADS) {
+        int4 v = make_int4(-1, 0, 0, 0);
+        if (e < bfirst[3 * 64]) {
+            int lo = 0, hi = L;  // smallest group whose blocks end after e
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (bfirst[mid + 1] > e) hi = mid; else lo = mid + 1;
+            }
+            const int b = e - bfirst[lo];
+            v = make_int4(lo, goff[lo] + 32 * b, min(32, tot[lo] - 32 * b), 0);
+        }
+        blocktab[e] = v;
     }
-    for (int b = bfirst[3 * 64] + threadIdx.x; b < n_blocks; b += PREP_THREADS) blocktab[b] = make_int4(-1, 0, 0, 0);
 
     // pass 2: placement
     for (int tb = t0; tb < t1; tb += 64) {
         const int t = tb + lane;
         const int key_l = row_key(t, false);
-        unsigned long long rem = __ballot(key_l >= 0);
-        while (rem) {
-            const int lead = __ffsll((long long)rem) - 1;
-            const int key = __shfl(key_l, lead);
-            const unsigned long long m = __ballot(key_l == key);
-            const int base = goff[key] + my_cnt[key];
-            if (key_l == key) {
-                const unsigned long long below = m & ((1ull << lane) - 1ull);
-                perm[base + __popcll(below)] = t;
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane == lead) my_cnt[key] = my_cnt[key] + __popcll(m);
-            __builtin_amdgcn_wave_barrier();
-            rem &= ~m;
-        }
+        const unsigned long long same = same_key_lanes(key_l);
+        // every lane reads its group's cursor before the group's first lane advances it
+        if (same) perm[goff[key_l] + my_cnt[key_l] + __popcll(same & lanes_below)] = t;
+        __builtin_amdgcn_wave_barrier();
+        if (same && !(same & lanes_below)) atomicAdd(&my_cnt[key_l], __popcll(same));
+        __builtin_amdgcn_wave_barrier();
     }
 }
 

@@ -1,20 +1,19 @@
 // LoRA shrink for bf16 batches: S[t,:] = x[t,:] . A[a] for adapted rows only, on bf16 MFMA with
 // fp32 accumulation.  Rows come from the grouped list (adapter-major, stable): a workgroup takes
-// 32 rows of ONE adapter and one slice of the hidden dimension.
+// 32 rows of ONE adapter and walks the whole hidden dimension.
 //
-// The kernel is latency-bound work (a few MB), so it is built around as few memory round trips as
-// possible: a workgroup issues ALL loads of a 128 KB chunk up front as direct-to-LDS copies (the
-// gathered token rows, 16-byte chunks XOR-swizzled by row; the adapter's A slice copied verbatim,
-// it is already k-major), waits once, then runs the MFMAs out of LDS (ds_read_b128 for tokens,
-// the transposing ds_read_b64_tr_b16 for A).  The hidden dimension is cut into up to four slices
-// handled by different workgroups so that more CUs pull data at once.
+// The kernel moves a few MB and is bound by how many bytes one compute unit keeps in flight, so
+// it streams: the hidden dimension is cut into chunks, two LDS buffers alternate, and all loads
+// of a chunk are issued at once as direct-to-LDS copies (the gathered token rows, 16-byte chunks
+// XOR-swizzled by row; the adapter's A rows copied verbatim, they are already k-major) while the
+// previous chunk runs its MFMAs out of LDS (ds_read_b128 for tokens, the transposing
+// ds_read_b64_tr_b16 for A).  The four wavefronts split every chunk's k steps; their partial sums
+// are added in fixed order at the end.
 //
-// Slices are NOT summed here (that would need a grid-wide exchange).  Each slice's fp32 result is
-// stored as two bf16 numbers per element, P_s = hi_s + lo_s with hi = bf16(P), lo = bf16(P - hi),
-// and the projection kernel treats [hi_0 | lo_0 | hi_1 | lo_1 | ...] as one long K dimension
-// against B stacked the same number of times: the expand runs on the same bf16 MFMA pipe as the
-// base GEMM, keeps ~16 mantissa bits of every slice, and the sum over slices happens inside the
-// fp32 MFMA accumulator in a fixed order.
+// The fp32 result is handed on as two bf16 numbers per element, S = hi + lo with hi = bf16(S),
+// lo = bf16(S - hi), stored as [hi_0..hi_{r-1} | lo_0..lo_{r-1}] per row: the projection kernel
+// runs the expand on the same bf16 MFMA pipe as the base GEMM ([S_hi | S_lo] against [B ; B])
+// and still sees ~16 mantissa bits of S.
 #include "alora_internal.h"
 
 namespace alora {
@@ -26,49 +25,35 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 __device__ __attribute__((aligned(256))) uint32_t g_zero_page[64];  // zero-initialised
 
 constexpr int SHRINK_ROWS = 32;
-constexpr int SHRINK_MAX_SLICES = 4;
 
-// chunk of the hidden dimension that fits LDS at once (tokens 32 x chunk, A chunk x rank)
-static inline int shrink_chunk_len(int r) { return r <= 32 ? 1024 : 512; }
-
-int shrink_slices(int H, int r)
-{
-    const int chunks = (H + shrink_chunk_len(r) - 1) / shrink_chunk_len(r);
-    return chunks < SHRINK_MAX_SLICES ? chunks : SHRINK_MAX_SLICES;
-}
-// hidden-dimension extent of one slice: a whole number of chunks
-static inline int shrink_slice_len(int H, int r)
-{
-    const int c = shrink_chunk_len(r);
-    const int chunks = (H + c - 1) / c, ks = shrink_slices(H, r);
-    return ((chunks + ks - 1) / ks) * c;
-}
-
-// KSL: chunk length; NT: 32-wide rank tiles (1 for rank <= 32, else 2)
+// KSL: hidden-dimension chunk per LDS buffer; NT: 32-wide rank tiles (1 for rank <= 32, else 2)
 template <int KSL, int NT>
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restrict__ x, PtrTable A,
                                                           const int32_t *__restrict__ perm,
-                                                          const int4 *__restrict__ blocktab, int L, int H, int r,
-                                                          int slice_len, bf16_t *__restrict__ S_hl)
+                                                          const int4 *__restrict__ blocktab, int L, int H, int r, uint32_t x_bytes,
+                                                          bf16_t *__restrict__ S_hl)
 {
     constexpr int XROW_BYTES = KSL * 2;
     constexpr int CPR = KSL / 8;                 // 16-byte chunks per token row
     constexpr int X_BYTES = SHRINK_ROWS * XROW_BYTES;
-    constexpr int A_BYTES = 65536;               // KSL * rank * 2 <= 64 KB for both instantiations
-    __shared__ __attribute__((aligned(16))) unsigned char xs[X_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char as[A_BYTES + 256];
+    constexpr int A_BYTES = KSL * 32 * NT * 2;   // KSL rows of up to 32*NT rank columns
+    constexpr int XI = X_BYTES / 1024 / 4;       // token-copy instructions per wavefront and chunk
+    constexpr int AI = A_BYTES / 1024 / 4;       // A-copy instructions per wavefront and chunk
+    constexpr int RPI = 64 / CPR;                // token rows per copy instruction (1 or 2)
+    static_assert(CPR == 64 || CPR == 32, "chunk layout");
+    // separate LDS objects per buffer: reads of one do not wait for copies into the other
+    __shared__ __attribute__((aligned(16))) unsigned char xs0[X_BYTES], xs1[X_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char as0[A_BYTES + 256], as1[A_BYTES + 256];
     __shared__ float red[4][NT][32][33];
     __shared__ int rows_t[SHRINK_ROWS];
 
     // which (adapter, 32-row block) is this workgroup?  (table written by the grouping kernel)
-    const int4 entry = blocktab[blockIdx.y];
+    const int4 entry = blocktab[blockIdx.x];
     const int a = entry.x, j0 = entry.y, cnt = entry.z;
     if (a < 0 || a >= L) return;  // unused entry or the base group; uniform across the workgroup
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KS = gridDim.x, slice = blockIdx.x;
-    const int k_begin = slice * slice_len, k_end = min(H, k_begin + slice_len);
     const bf16_t *Aa = (const bf16_t *)A.p[a];
 
     if (tid < SHRINK_ROWS) rows_t[tid] = tid < cnt ? perm[j0 + tid] : -1;
@@ -83,61 +68,110 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[nt][e] = 0.f;
 
-    for (int ks0 = k_begin; ks0 < k_end; ks0 += KSL) {
-        const int klen = min(KSL, k_end - ks0);  // multiple of 64
-        // ---- all loads of the chunk, up front -----------------------------------------------
-        // A chunk: rows ks0 .. ks0+klen of [H, r], contiguous in memory, copied verbatim
-        {
-            const size_t a_bytes = (size_t)klen * r * 2;
-            const unsigned char *abase = (const unsigned char *)(Aa + (size_t)ks0 * r);
+    // all copies of the chunk starting at hidden index ks0
+    // Buffer descriptors: reads past the end of A (a short last chunk) return zeros by themselves;
+    // masked token lanes get an offset past the end of x.
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void *)Aa, 0, H * r * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)x, 0, (int)x_bytes, 0x00020000);
+    // per-lane byte offsets of the token copies at hidden index 0 (0xffffffff = masked)
+    uint32_t xoff[XI];
+    int xchunk[XI];
 #pragma unroll
-            for (int qq = 0; qq < 16; ++qq) {
-                const int q = w * 16 + qq;
-                const size_t off = (size_t)q * 1024 + 16 * lane;
-                const void *src = off < a_bytes ? (const void *)(abase + off) : (const void *)g_zero_page;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                 (__attribute__((address_space(3))) void *)((lds_byte *)as + q * 1024),
-                                                 16, 0, 0);
-            }
-        }
-        // tokens: instruction q copies 64 chunks of row q / (CPR/64); lane -> physical chunk, which
-        // holds logical chunk (physical ^ (row % 16))
-        constexpr int XI = SHRINK_ROWS * CPR / 64;
-        constexpr int PARTS = CPR / 64;
+    for (int qq = 0; qq < XI; ++qq) {
+        const int row = (w * XI + qq) * RPI + lane / CPR;
+        const int t = rows_t[row];
+        xchunk[qq] = (lane % CPR) ^ (row & 15);
+        xoff[qq] = t >= 0 ? (uint32_t)t * (uint32_t)H * 2u + 16u * xchunk[qq] : 0xffffffffu;
+    }
+    auto issue = [&](int ks0, unsigned char *xs, unsigned char *as) {
+        const int klen = min(KSL, H - ks0);  // multiple of 64
 #pragma unroll
-        for (int qq = 0; qq < XI / 4; ++qq) {
-            const int q = w * (XI / 4) + qq;
-            const int row = q / PARTS, part = q % PARTS;
-            const int t = rows_t[row];
-            const int c = (part * 64 + lane) ^ (row & 15);
-            const bool ok = t >= 0 && 8 * c < klen;
-            const void *src = ok ? (const void *)(x + (size_t)t * H + ks0 + 8 * c) : (const void *)g_zero_page;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)((lds_byte *)xs + q * 1024), 16,
-                                             0, 0);
+        for (int qq = 0; qq < AI; ++qq) {
+            const int q = w * AI + qq;
+            const uint32_t off = (uint32_t)q * 1024u + 16u * lane;
+            // rows ks0 .. ks0+klen of [H, r] are contiguous; what lies beyond them in the buffer is
+            // either past the end of A (zeros) or masked here
+            const uint32_t vo = off < (uint32_t)klen * r * 2 ? off : 0xffffffffu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void *)((lds_byte *)as + q * 1024),
+                                                     16, vo, (uint32_t)ks0 * r * 2, 0, 0);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-
-        // ---- MFMA out of LDS; the four wavefronts interleave over the 16-wide k steps ---------
-        for (int ks = w; ks < klen / 16; ks += 4) {
+        // tokens: instruction q copies RPI rows; lane -> physical chunk, holding logical chunk
+        // (physical ^ (row % 16))
+#pragma unroll
+        for (int qq = 0; qq < XI; ++qq) {
+            const int q = w * XI + qq;
+            const uint32_t vo = 8 * xchunk[qq] < klen ? xoff[qq] : 0xffffffffu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)((lds_byte *)xs + q * 1024),
+                                                     16, vo, (uint32_t)ks0 * 2, 0, 0);
+        }
+    };
+    // MFMAs of one chunk out of LDS; the four wavefronts interleave over the 16-wide k steps
+    // (a short last chunk is zero-filled by the copies, so every chunk runs all its k steps and the
+    // loop unrolls into straight-line code)
+    // The LDS reads are written as assembly with their own wait: the compiler cannot tell which of
+    // the in-flight copies a read depends on and would otherwise drain all of them (including the
+    // next chunk's) before the first read.  The explicit waits around compute() order them.
+    auto compute = [&](const unsigned char *xs, const unsigned char *as) {
+        const uint32_t xbase = (uint32_t)(uintptr_t)(const lds_byte *)xs + li * XROW_BYTES;
+        const uint32_t abase = (uint32_t)(uintptr_t)(const lds_byte *)as + (8 * lh + (s16 >> 2)) * row_bytes +
+                               (16 * blk + 4 * (s16 & 3)) * 2;
+#pragma unroll
+        for (int kq = 0; kq < KSL / 64; ++kq) {
+            const int ks = 4 * kq + w;
             const int c = 2 * ks + lh;
-            const bf16x8 xf = *(const __attribute__((address_space(3))) bf16x8 *)((const lds_byte *)xs +
-                                                                                   li * XROW_BYTES + ((c ^ (li & 15)) << 4));
+            const uint32_t xa = xbase + ((c ^ (li & 15)) << 4);
+            u32x4 xv;
+            u32x2 lo[NT], hi[NT];
+            uint32_t pa[NT], pb[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int kk = 16 * ks + 8 * lh + (s16 >> 2);
-                const int col = nt * 32 + 16 * blk + 4 * (s16 & 3);
-                const lds_byte *p = (const lds_byte *)as + kk * row_bytes + col * 2;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(p + 4 * row_bytes));
-                const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, __builtin_bit_cast(bf16x8, v), acc[nt], 0, 0, 0);
+                pa[nt] = abase + 16 * ks * row_bytes + nt * 64;
+                pb[nt] = pa[nt] + 4 * row_bytes;
+            }
+            if constexpr (NT == 1) {
+                asm volatile("ds_read_b128 %0, %3\n\tds_read_b64_tr_b16 %1, %4\n\tds_read_b64_tr_b16 %2, %5\n\t"
+                             "s_waitcnt lgkmcnt(0)"
+                             : "=&v"(xv), "=&v"(lo[0]), "=&v"(hi[0])
+                             : "v"(xa), "v"(pa[0]), "v"(pb[0])
+                             : "memory");
+            } else {
+                asm volatile("ds_read_b128 %0, %5\n\tds_read_b64_tr_b16 %1, %6\n\tds_read_b64_tr_b16 %2, %7\n\t"
+                             "ds_read_b64_tr_b16 %3, %8\n\tds_read_b64_tr_b16 %4, %9\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(xv), "=&v"(lo[0]), "=&v"(hi[0]), "=&v"(lo[NT - 1]), "=&v"(hi[NT - 1])
+                             : "v"(xa), "v"(pa[0]), "v"(pb[0]), "v"(pa[NT - 1]), "v"(pb[NT - 1])
+                             : "memory");
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const u32x4 av = {lo[nt].x, lo[nt].y, hi[nt].x, hi[nt].y};
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xv),
+                                                                  __builtin_bit_cast(bf16x8, av), acc[nt], 0, 0, 0);
             }
         }
-        __syncthreads();  // LDS is overwritten by the next chunk
+    };
+    // wait until only the `newer` most recent copies of this wavefront are outstanding, then meet
+    // the other wavefronts (whose copies the MFMAs read as well)
+#define SHRINK_WAIT_OLDER() asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(XI + AI) : "memory")
+#define SHRINK_WAIT_ALL() asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory")
+#define SHRINK_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+    const int nchunks = (H + KSL - 1) / KSL;
+    issue(0, xs0, as0);
+    if (nchunks > 1) issue(KSL, xs1, as1);
+    for (int i = 0; i < nchunks; i += 2) {
+        if (i + 1 < nchunks) SHRINK_WAIT_OLDER(); else SHRINK_WAIT_ALL();
+        compute(xs0, as0);
+        SHRINK_BARRIER();  // every wavefront is done with buffer 0
+        if (i + 2 < nchunks) issue((i + 2) * KSL, xs0, as0);
+        if (i + 1 >= nchunks) break;
+        if (i + 2 < nchunks) SHRINK_WAIT_OLDER(); else SHRINK_WAIT_ALL();
+        compute(xs1, as1);
+        SHRINK_BARRIER();
+        if (i + 3 < nchunks) issue((i + 3) * KSL, xs1, as1);
     }
+#undef SHRINK_WAIT_OLDER
+#undef SHRINK_WAIT_ALL
+#undef SHRINK_BARRIER
 
     // D[row][col]: lane holds col = lane % 32, rows 8g + 4*lh + jj in register 4g + jj
 #pragma unroll
@@ -148,7 +182,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
             for (int jj = 0; jj < 4; ++jj) red[w][nt][8 * g + 4 * lh + jj][li] = acc[nt][4 * g + jj];
     __syncthreads();
 
-    // ---- add the four wavefronts in fixed order, split, store this slice's columns --------------
+    // ---- add the four wavefronts in fixed order, split into (hi, lo), store -----------------------
     for (int idx = tid; idx < 32 * 32 * NT; idx += 256) {
         const int col = idx % (32 * NT), row = idx / (32 * NT);
         const int tt = rows_t[row];
@@ -157,7 +191,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
         const float s = ((red[0][nt][row][c] + red[1][nt][row][c]) + red[2][nt][row][c]) + red[3][nt][row][c];
         const uint32_t hi = f32_to_bf16_bits(s);
         const uint32_t lo = f32_to_bf16_bits(s - bf16_bits_to_f32(hi));
-        bf16_t *dst = S_hl + ((size_t)tt * KS + slice) * 2 * r;
+        bf16_t *dst = S_hl + (size_t)tt * 2 * r;
         dst[col] = (bf16_t)hi;
         dst[r + col] = (bf16_t)lo;
     }
@@ -166,14 +200,13 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;
-    const dim3 grid(shrink_slices(f.H, f.r), f.n_blocks);
-    const int sl = shrink_slice_len(f.H, f.r);
+    const dim3 grid(f.n_blocks);
     if (f.r <= 32)
-        hipLaunchKernelGGL((shrink_bf16_kernel<1024, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
-                           f.blocktab, f.L, f.H, f.r, sl, (bf16_t *)f.S);
+        hipLaunchKernelGGL((shrink_bf16_kernel<512, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
+                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), (bf16_t *)f.S);
     else
-        hipLaunchKernelGGL((shrink_bf16_kernel<512, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
-                           f.blocktab, f.L, f.H, f.r, sl, (bf16_t *)f.S);
+        hipLaunchKernelGGL((shrink_bf16_kernel<256, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
+                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), (bf16_t *)f.S);
     return (int)hipGetLastError();
 }
 
