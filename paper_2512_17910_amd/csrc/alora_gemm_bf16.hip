@@ -14,8 +14,15 @@
 // Data movement (gfx950):
 //   - global -> LDS with buffer loads that write LDS directly (no VGPR staging); the buffer
 //     descriptor's range check returns zeros for token rows past T, masked lanes get an
-//     out-of-range offset.  Two LDS stages of 64 KB; one barrier per 64-wide K-slice.
-//   - token tile in LDS: [row][64 k], 16-byte chunks XOR-swizzled by (row/2)%8, read with
+//     out-of-range offset.
+//   - the K dimension runs through a ring of four 32 KB LDS stages, 32 k per stage.  The slices a
+//     tile consumes form one sequence: first the expand slices (one or more per adapter present in
+//     the tile), then the base slices.  While slice i is multiplied, the first fragments of slice
+//     i+1 are already fetched from LDS, and slices i+2 and i+3 are in flight from memory; the
+//     copies of slice i+3 are issued one per three MFMAs, which keeps the demand on the vector
+//     memory pipe (64 B/clk per CU) uniform.  One barrier per slice, placed where the MFMAs that
+//     follow it already have their operands in registers.
+//   - token tile in LDS: [row][32 k], 16-byte chunks XOR-swizzled by (row/4)%4, read with
 //     ds_read_b128.  Weight tile in LDS: k-major exactly as in global memory ([k][256 n]),
 //     16-byte chunks XOR-swizzled by 4*(k%4), read with the transposing LDS load
 //     (ds_read_b64_tr_b16), which hands each lane four consecutive k of one feature column.
@@ -27,10 +34,11 @@
 
 namespace alora {
 
-constexpr int BM = 256, BK = 64;
+constexpr int BM = 256, BK = 32;
+constexpr int KBLK = 64;     // granularity of the hidden dimension the host plans splits in
 constexpr int WPITCH = 512;  // bytes per k row of the weight tile in LDS (room for 256 features)
 constexpr int GEMM_THREADS = 256;
-constexpr uint32_t STAGE_BYTES = 65536, W_OFF = 32768;
+constexpr uint32_t STAGE_BYTES = 32768, W_OFF = 16384;
 constexpr uint32_t OOR = 0x80000000u;  // buffer offset that is out of range for every descriptor
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -47,21 +55,32 @@ struct GemmArgs {
     int T, H, Nq, Nkv, N, L, r;
     int kx;  // length of the expand K dimension: (hi | lo) x r
     int mtiles, ntiles;
-    int kps;          // split mode: K-slices per split
+    int kps;          // split mode: 32-wide K-slices per split
     float *partial;   // split mode: [splits][T][N] fp32
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+// Buffer descriptor of a raw byte buffer (stride 0, 32-bit data format): offsets at or past
+// `bytes` read as zero.
+typedef u32x4 rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
-    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+    const uint64_t p = (uint64_t)base;
+    const rsrc_t r = {(uint32_t)p, (uint32_t)(p >> 32) & 0xffffu, bytes, 0x00020000u};
+    return r;
 }
 
-__device__ __forceinline__ void load_lds16(__amdgpu_buffer_rsrc_t rsrc, lds_byte *dst, uint32_t voffset,
-                                           uint32_t soffset)
+// 64 lanes x 16 bytes from the buffer straight into LDS at lds_addr + 16*lane.  Written as an
+// assembly statement: the kernel orders these copies against its LDS reads itself (wait counts and
+// barriers in the main loop), which the compiler's own bookkeeping of such loads would override
+// with waits for all of them.
+__device__ __forceinline__ void load_lds16(rsrc_t rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset)
 {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)dst, 16, voffset,
-                                             soffset, 0, 0);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory");
 }
+__device__ __forceinline__ uint32_t lds_addr_of(const lds_byte *p) { return (uint32_t)(uintptr_t)p; }
 
 __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p)
 {
@@ -80,15 +99,21 @@ template <int NTW, bool SPLIT>
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B)
 {
     constexpr int BN = 64 * NTW;
-    // two separate LDS objects, so that the compiler can tell that reads of one stage do not
-    // depend on the in-flight direct loads into the other
+    // separate LDS objects, so that the compiler can tell that reads of one stage do not depend on
+    // the in-flight direct loads into the others
     __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char stage2[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char stage3[STAGE_BYTES];
     __shared__ int arow[BM];                       // effective adapter per tile row
     __shared__ int present[ALORA_MAX_ADAPTERS];
+    __shared__ int plist[ALORA_MAX_ADAPTERS];      // adapters present in this tile, ascending
+    __shared__ int n_present;
     __shared__ int64_t slot_lds[BM];               // cache slot per tile row (-1: no K/V write)
     lds_byte *const st0 = (lds_byte *)stage0;
     lds_byte *const st1 = (lds_byte *)stage1;
+    lds_byte *const st2 = (lds_byte *)stage2;
+    lds_byte *const st3 = (lds_byte *)stage3;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -112,6 +137,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     const int rows_valid = min(g.T - m0, BM);
 
     // ---- 1. this tile's rows: effective adapter (from the grouping kernel), cache slot; adapters present
+    int n_exp = 0;           // expand slices ahead of the base slices
+    int epa = 0;             // expand slices per adapter
     {
         const int t = m0 + tid;
         int a = -1;
@@ -122,33 +149,38 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         __syncthreads();
         if (a >= 0) present[a] = 1;
         __syncthreads();
+        if (tid < 64) {
+            const bool p0 = present[tid] != 0, p1 = present[64 + tid] != 0;
+            const uint64_t b0 = __ballot(p0), b1 = __ballot(p1);
+            const uint64_t below = (1ull << tid) - 1ull;
+            const int c0 = __popcll(b0);
+            if (p0) plist[__popcll(b0 & below)] = tid;
+            if (p1) plist[c0 + __popcll(b1 & below)] = 64 + tid;
+            if (tid == 0) n_present = c0 + __popcll(b1);
+        }
+        __syncthreads();
+        if (!SPLIT) {
+            epa = (g.kx + BK - 1) / BK;
+            n_exp = __builtin_amdgcn_readfirstlane(n_present) * epa;
+        }
     }
 
-    // ---- per-lane constants of the global -> LDS copies ------------------------------------
-    // token tile: instruction ii of wave w fills rows 64w + 8ii .. +7; lane -> row +lane/8, physical
-    // chunk lane%8, which holds logical chunk (lane%8) ^ swizzle(row)
-    int xrow[8], xchunk[8];
-#pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-        xrow[ii] = 64 * w + 8 * ii + (lane >> 3);
-        xchunk[ii] = (lane & 7) ^ ((xrow[ii] >> 1) & 7);
-    }
-    // weight tile: instruction jj of wave w fills k rows 16w + 2jj, +1; lane -> row +lane/32, physical
+    // ---- per-lane geometry of the global -> LDS copies ----------------------------------------
+    // token tile: instruction ii of wave w fills rows 64w + 16ii .. +15; lane -> row +lane/4, physical
+    // chunk lane%4, which holds logical chunk (lane%4) ^ swizzle(row)
+    auto x_row = [&](int ii, int ln) { return 64 * w + 16 * ii + (ln >> 2); };
+    auto x_chunk = [&](int ii, int ln) { return (ln & 3) ^ ((x_row(ii, ln) >> 2) & 3); };
+    // weight tile: instruction jj of wave w fills k rows 8w + 2jj, +1; lane -> row +lane/32, physical
     // chunk lane%32 holding logical chunk (lane%32) ^ 4*(k%4)
-    int wk[8], wchunk[8];
-    bool wcol_ok[8];
-#pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-        wk[jj] = 16 * w + 2 * jj + (lane >> 5);
-        wchunk[jj] = (lane & 31) ^ ((wk[jj] & 3) << 2);
-        wcol_ok[jj] = 8 * wchunk[jj] < BN && n0 + 8 * wchunk[jj] < g.N;
-    }
+    auto w_k = [&](int jj, int ln) { return 8 * w + 2 * jj + (ln >> 5); };
+    auto w_chunk = [&](int jj, int ln) { return (ln & 31) ^ ((w_k(jj, ln) & 3) << 2); };
+    auto w_col_ok = [&](int jj, int ln) { return (8 * w_chunk(jj, ln) < BN) & (n0 + 8 * w_chunk(jj, ln) < g.N); };
 
     // ---- per-lane LDS read addresses of the MFMA operands ----------------------------------
     uint32_t xaddr;  // token fragment: row wt*128 + li (+32 b), chunk 2ks + lh
     {
         const int row0 = wt * 128 + li;
-        xaddr = (uint32_t)row0 * (BK * 2) + (uint32_t)((lh ^ ((row0 >> 1) & 7)) << 4);
+        xaddr = (uint32_t)row0 * (BK * 2) + (uint32_t)((lh ^ ((row0 >> 2) & 3)) << 4);
     }
     uint32_t waddr[NTW];  // weight fragments via transposing read; see read_w_frag
     {
@@ -168,141 +200,171 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-    auto issue = [&](__amdgpu_buffer_rsrc_t rx, const uint32_t (&vx)[8], uint32_t sx, __amdgpu_buffer_rsrc_t rw,
-                     const uint32_t (&vw)[8], uint32_t sw, lds_byte *st) {
+    // ---- the slice sequence -------------------------------------------------------------------
+    const rsrc_t rx = make_rsrc(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
+    const rsrc_t rw = make_rsrc(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
+    const rsrc_t rs = make_rsrc(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
+    uint32_t vxb[4], vwb[4];
 #pragma unroll
-        for (int ii = 0; ii < 8; ++ii)
-            load_lds16(rx, st + (uint32_t)(64 * w + 8 * ii) * (BK * 2), vx[ii], sx);
+    for (int ii = 0; ii < 4; ++ii) vxb[ii] = (uint32_t)(x_row(ii, lane) * g.H + 8 * x_chunk(ii, lane)) * 2;
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj)
-            load_lds16(rw, st + W_OFF + (uint32_t)(16 * w + 2 * jj) * WPITCH, vw[jj], sw);
+    for (int jj = 0; jj < 4; ++jj) vwb[jj] = w_col_ok(jj, lane) ? (uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
+    const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
+    // base K-slices of this workgroup: all of them, or the range of its split
+    const int kt0 = SPLIT ? (int)blockIdx.y * g.kps : 0;
+    const int KT = SPLIT ? min(g.H / BK, kt0 + g.kps) : g.H / BK;
+    const int n_base = KT - kt0;
+
+    // copies of one 32-wide slice: this wavefront's four token-tile (c = 0..3) and four weight-tile
+    // (c = 4..7) instructions
+    auto copy = [&](int c, rsrc_t r_x, const uint32_t (&vx)[4], uint32_t sx, rsrc_t r_w, const uint32_t (&vw)[4],
+                    uint32_t sw, uint32_t st) {
+        if (c < 4) load_lds16(r_x, st + (uint32_t)(64 * w + 16 * c) * (BK * 2), vx[c], sx);
+        else load_lds16(r_w, st + W_OFF + (uint32_t)(8 * w + 2 * (c - 4)) * WPITCH, vw[c - 4], sw);
+    };
+    // Base slice s of this workgroup.  Slices past the end repeat the last one: every step issues
+    // the same number of copies, which is what the in-order wait counts assume.
+    auto issue_base = [&](int s, uint32_t st) {
+        const int kb = kt0 + min(s, n_base - 1);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) copy(c, rx, vxb, kb * xstep, rw, vwb, kb * wstep, st);
     };
 
     // MFMA fragments of one 16-wide k step
+    auto read_x = [&](const lds_byte *base, int ks, int b) {
+        return *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
+    };
+    auto read_w = [&](const lds_byte *base, int ks, int a) { return read_w_frag(base + (waddr[a] + ks * 16 * WPITCH)); };
     auto load_frags = [&](const lds_byte *base, int ks, bf16x8 (&wf)[NTW], bf16x8 (&xf)[4]) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-            xf[b] = *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
+        for (int b = 0; b < 4; ++b) xf[b] = read_x(base, ks, b);
 #pragma unroll
-        for (int a = 0; a < NTW; ++a) wf[a] = read_w_frag(base + (waddr[a] + ks * 16 * WPITCH));
+        for (int a = 0; a < NTW; ++a) wf[a] = read_w(base, ks, a);
     };
-    // one 64-wide K-slice out of LDS; the fragments of step ks+1 are fetched before the MFMAs of
-    // step ks are issued, so LDS latency hides behind the matrix pipe
-    auto compute = [&](const lds_byte *base) {
-        bf16x8 wf[2][NTW], xf[2][4];
-        load_frags(base, 0, wf[0], xf[0]);
+    auto mfmas = [&](const bf16x8 (&wf)[NTW], const bf16x8 (&xf)[4]) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) load_frags(base, ks + 1, wf[(ks + 1) & 1], xf[(ks + 1) & 1]);
+        for (int a = 0; a < NTW; ++a)
 #pragma unroll
-            for (int a = 0; a < NTW; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b], 0, 0, 0);
-        }
-    };
-    // Instruction order handed to the scheduler for one K-slice region (global->LDS copies of the
-    // next slice + the MFMAs of this one): first fragments and a few copies while they arrive,
-    // then one LDS read and one copy behind every MFMA, so neither queue blocks the matrix pipe.
-    auto pipeline_order = [&](bool with_copies) {
-        constexpr int NREAD = 4 + 2 * NTW, NMFMA = 4 * NTW;
-        int copies = with_copies ? 16 : 0;
-        __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);
-        if (copies) { __builtin_amdgcn_sched_group_barrier(0x020, 4, 0); copies -= 4; }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16 - 1; ++ks) {
-#pragma unroll
-            for (int i = 0; i < NMFMA; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (i < NREAD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (copies > 0) { __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); --copies; }
-            }
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA, 0);
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
     };
 
+    bf16x8 wf0[NTW], xf0[4], wf1[NTW], xf1[4];
+
+    // fill the ring with base slices 0, 1, 2; their latency also covers the expand phase
+    const uint32_t sa0 = lds_addr_of(st0), sa1 = lds_addr_of(st1), sa2 = lds_addr_of(st2), sa3 = lds_addr_of(st3);
+    issue_base(0, sa0);
+    issue_base(1, sa1);
+    issue_base(2, sa2);
+
     // ---- 2. expand first, then select ------------------------------------------------------
-    bool any_adapter = false;
-    if (!SPLIT && g.L > 0) {
-        const __amdgpu_buffer_rsrc_t rs =
-            make_rsrc(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
-        for (int a = 0; a < g.L; ++a) {
-            if (!present[a]) continue;  // uniform (LDS broadcast)
-            any_adapter = true;
-            const __amdgpu_buffer_rsrc_t rb =
+    // One slice at a time through the fourth stage (few slices, not pipelined): 32 k of
+    // [S_hi | S_lo] for the rows of adapter a (zeros elsewhere) against the matching rows of [B_a ; B_a].
+    if (!SPLIT && n_exp > 0) {
+        for (int e = 0; e < n_exp; ++e) {
+            const int j = e / epa, k0 = (e - j * epa) * BK;
+            const int a = __builtin_amdgcn_readfirstlane(plist[j]);
+            const rsrc_t rb =
                 make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(g.r * g.N - n0) * 2);
-            for (int k0 = 0; k0 < g.kx; k0 += BK) {
-                uint32_t vx[8], vw[8];
+            uint32_t vx[4], vw[4];
 #pragma unroll
-                for (int ii = 0; ii < 8; ++ii) {
-                    const int kk = k0 + 8 * xchunk[ii];
-                    const bool ok = arow[xrow[ii]] == a && kk < g.kx;
-                    vx[ii] = ok ? (uint32_t)(xrow[ii] * g.kx + kk) * 2 : OOR;
-                }
-#pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
-                    const int kk = k0 + wk[jj];
-                    const int srow = kk % g.r;
-                    const bool ok = kk < g.kx && wcol_ok[jj];
-                    vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * wchunk[jj]) * 2 : OOR;
-                }
-                issue(rs, vx, 0, rb, vw, 0, st0);
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-                compute(st0);
-                __syncthreads();
+            for (int ii = 0; ii < 4; ++ii) {
+                const int row = x_row(ii, lane), kk = k0 + 8 * x_chunk(ii, lane);
+                const bool ok = (arow[row] == a) & (kk < g.kx);
+                vx[ii] = ok ? (uint32_t)(row * g.kx + kk) * 2 : OOR;
             }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int kk = k0 + w_k(jj, lane);
+                const int srow = kk >= g.r ? kk - g.r : kk;   // [B ; B]: the hi and the lo half meet the same rows
+                const bool ok = (kk < g.kx) & w_col_ok(jj, lane);
+                vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) copy(c, rs, vx, 0, rb, vw, 0, sa3);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            load_frags(st3, 0, wf0, xf0);
+            load_frags(st3, 1, wf1, xf1);
+            mfmas(wf0, xf0);
+            mfmas(wf1, xf1);
+            __syncthreads();
         }
-    }
-    if (any_adapter) {
+        // The select is written as a masked store of zero into the accumulator registers themselves,
+        // so that the accumulators do not travel through the vector registers the main loop needs.
+        // Assembly statements get no automatic hazard padding: let the last MFMAs drain first.
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const bool keep = arow[wt * 128 + b * 32 + li] >= 0;
+            if (arow[wt * 128 + b * 32 + li] < 0) {
 #pragma unroll
-            for (int a = 0; a < NTW; ++a)
+                for (int a = 0; a < NTW; ++a)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[a][b][e] = keep ? acc[a][b][e] : 0.f;
+                    for (int e = 0; e < 16; ++e) {
+                        float t = acc[a][b][e];
+                        asm volatile("v_accvgpr_write_b32 %0, 0" : "+a"(t));
+                        acc[a][b][e] = t;
+                    }
+            }
         }
+        asm volatile("s_nop 7" ::: "memory");
     }
 
     // ---- 3. base GEMM ---------------------------------------------------------------------
-    {
-        const __amdgpu_buffer_rsrc_t rx = make_rsrc(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
-        const __amdgpu_buffer_rsrc_t rw = make_rsrc(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
-        uint32_t vx[8], vw[8];
+    // step s: multiplies slice s (stage cur); fetches the first fragments of slice s+1 (stage nxt);
+    // issues the copies of slice s+3 into the stage that slice s-1 occupied (tgt)
+    // Within a step the source order is the issue order: behind every MFMA one fragment read for
+    // the next 16 k until they are all issued, and one copy behind every third MFMA, which keeps the
+    // demand on the vector memory pipe (64 B/clk per CU) uniform.
+    auto step = [&](int s, const lds_byte *cur, const lds_byte *nxt, uint32_t tgt) {
+        // this wavefront's copies of slices <= s+1 have landed (the 8 of slice s+2 may be in flight);
+        // behind the barrier that holds for every wavefront, and all of them are done reading tgt
+        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+        const int kb = kt0 + min(s + 3, n_base - 1);
+        const uint32_t sx = kb * xstep, sw = kb * wstep;
+        constexpr int NM = 4 * NTW, CI = NTW == 2 ? 2 : 3;
 #pragma unroll
-        for (int ii = 0; ii < 8; ++ii) vx[ii] = (uint32_t)(xrow[ii] * g.H + 8 * xchunk[ii]) * 2;
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) vw[jj] = wcol_ok[jj] ? (uint32_t)(wk[jj] * g.N + 8 * wchunk[jj]) * 2 : OOR;
-        const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
-        // K-slices of this workgroup: all of them, or the range of its split
-        const int kt0 = SPLIT ? (int)blockIdx.y * g.kps : 0;
-        const int KT = SPLIT ? min(g.H / BK, kt0 + g.kps) : g.H / BK;
-        issue(rx, vx, kt0 * xstep, rw, vw, kt0 * wstep, st0);
-        // The copy of slice kt+1 is issued unconditionally inside the region that computes slice kt
-        // (past the end it re-reads the last slice into the idle stage), so that the scheduler can
-        // spread the copies between the MFMAs.
-        for (int kt = kt0; kt < KT; kt += 2) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            {
-                const int kn = min(kt + 1, KT - 1);
-                issue(rx, vx, kn * xstep, rw, vw, kn * wstep, st1);
-                compute(st0);
-                pipeline_order(true);
+        for (int gm = 0; gm < 2 * NM; ++gm) {
+            const int half = gm / NM, m = gm % NM, a = m / 4, b = m % 4;
+            if (half == 0) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[a], xf0[b], acc[a][b], 0, 0, 0);
+            else acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[a], xf1[b], acc[a][b], 0, 0, 0);
+            // unit u of the other fragment buffer, in the order the MFMAs will want them: the first
+            // five behind MFMAs 0..4, the rest behind every second MFMA after that
+            const int u = m < 5 ? m : ((m - 5) % 2 == 0 ? 5 + (m - 5) / 2 : -1);
+            if (u >= 0 && u < 4 + NTW) {
+                if (half == 0) {
+                    if (u == 0) wf1[0] = read_w(cur, 1, 0);
+                    else if (u <= 4) xf1[u - 1] = read_x(cur, 1, u - 1);
+                    else wf1[u - 4] = read_w(cur, 1, u - 4);
+                } else {
+                    if (u == 0) wf0[0] = read_w(nxt, 0, 0);
+                    else if (u <= 4) xf0[u - 1] = read_x(nxt, 0, u - 1);
+                    else wf0[u - 4] = read_w(nxt, 0, u - 4);
+                }
             }
-            if (kt + 1 >= KT) break;
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            {
-                const int kn = min(kt + 2, KT - 1);
-                issue(rx, vx, kn * xstep, rw, vw, kn * wstep, st0);
-                compute(st1);
-                pipeline_order(true);
+            if (gm % CI == 1 && gm / CI < 8) copy(gm / CI, rx, vxb, sx, rw, vwb, sw, tgt);
+        }
+        // the same order, spelled out for the instruction scheduler (MFMA, then the LDS reads of its unit)
+#pragma unroll
+        for (int gm = 0; gm < 2 * NM; ++gm) {
+            const int m = gm % NM;
+            const int u = m < 5 ? m : ((m - 5) % 2 == 0 ? 5 + (m - 5) / 2 : -1);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (u >= 0 && u < 4 + NTW) {
+                if (u >= 1 && u <= 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+    load_frags(st0, 0, wf0, xf0);
+    for (int s = 0; s < n_base; s += 4) {
+        step(s, st0, st1, sa3);
+        if (s + 1 < n_base) step(s + 1, st1, st2, sa0);
+        if (s + 2 < n_base) step(s + 2, st2, st3, sa1);
+        if (s + 3 < n_base) step(s + 3, st3, st0, sa2);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- 4. round and store ------------------------------------------------------------------
     // D[i][j]: i = feature (8g + 4*lh + jj, register 4g + jj), j = token (li).  Each wavefront turns
@@ -316,7 +378,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         constexpr int EP = 128 * NTW + 16;
         constexpr int LPR = 8 * NTW;           // lanes per row (four floats each)
         constexpr int RPI = 64 / LPR;
-        lds_byte *strip = ((w & 2) ? st1 : st0) + (w & 1) * 32768;
+        lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 4;
         float *out = g.partial + (size_t)blockIdx.y * g.T * g.N;
@@ -342,7 +404,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         constexpr int EP = 64 * NTW + 16;      // strip row pitch in bytes
         constexpr int LPR = 4 * NTW;           // lanes per row (16 bytes each)
         constexpr int RPI = 64 / LPR;          // rows per store instruction
-        lds_byte *strip = st0 + w * 16384;
+        lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 8;
         // destination of this lane's 8 features: 0 = q_out, 1 = K cache, 2 = V cache, -1 = none
@@ -400,7 +462,7 @@ GemmPlan plan_gemm(int T, int H, int N)
     constexpr int CUS = 256;                       // MI355X
     const int cand[3] = {4, 3, 2};
     const double unit[3] = {1.0, 0.78, 0.56};      // time of one K-slice relative to the 256-wide tile
-    const int mtiles = (T + BM - 1) / BM, KT = H / BK;
+    const int mtiles = (T + BM - 1) / BM, KT = H / KBLK;
     GemmPlan best = {4, 1, KT};
     double best_cost = 1e300;
     for (int i = 0; i < 3; ++i) {
@@ -455,7 +517,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projectio
     g.kx = 2 * f.r;
     g.mtiles = (f.T + BM - 1) / BM;
     g.ntiles = (f.N + 64 * plan.ntw - 1) / (64 * plan.ntw);
-    g.kps = plan.kps;
+    g.kps = plan.kps * (KBLK / BK);
     g.partial = f.partial;
     if (plan.ntw == 4) launch_ntw<4>(g, B, plan.splits, f.stream);
     else if (plan.ntw == 3) launch_ntw<3>(g, B, plan.splits, f.stream);
