@@ -56,8 +56,8 @@ static Layout make_layout(const alora_dims *d)
     l.aeff = o;    o += up256(T);
     l.perm = o;    o += up256(4 * T);
     l.offsets = o; o += up256(4 * (L + 2));
-    // f32: [T,r] fp32; bf16: [T,2r] bf16 (hi | lo halves of the fp32 shrink result)
-    l.S = o;       o += up256(T * r * 4);
+    // fp32 shrink result; the bf16 path keeps one partial per range of the hidden dimension
+    l.S = o;       o += up256(T * r * 4 * (d->dtype == ALORA_BF16 ? (size_t)ALORA_SHRINK_MAX_SPLITS : 1));
     l.n_blocks = group_blocks(d->T, d->n_adapters);
     l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
     l.partial = o;

@@ -8,7 +8,8 @@
 // rounds once to bf16 and stores q_out / the paged K and V slots.  Rows of the base group never
 // touch S or B, and their arithmetic does not depend on which rows are adapted: they come out
 // bit-identical to a call without adapters.  The low-rank term is plain fp32 FMAs (rank x 8 per
-// thread), S rebuilt from the (hi, lo) bf16 pair the shrink stored.
+// thread) on the fp32 shrink result: the fixed-order sum of the shrink's partials (or, when the
+// shrink ran as one range, hi + lo of the bf16 pair it stored).
 //
 // One thread per (row, 8 features): 1024 threads.  The kernel is a chain of dependent loads
 // (table entry -> row ids -> data), so everything after the row ids is issued at once: all
@@ -24,13 +25,14 @@ constexpr int FIN_COLS = 256;  // features per workgroup: 32 threads x 8 feature
 
 template <int SPLITS>
 __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restrict__ partial,
-                                                           const bf16_t *__restrict__ S_hl, PtrTable B,
+                                                           const void *__restrict__ S_any, int s_splits, PtrTable B,
                                                            const int32_t *__restrict__ perm,
                                                            const int4 *__restrict__ blocktab,
                                                            const int64_t *__restrict__ slot, bf16_t *__restrict__ q,
                                                            bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int T, int Nq,
                                                            int Nkv, int L, int r)
 {
+    const float *S_part = (const float *)S_any;
     __shared__ float s_lds[32][ALORA_MAX_RANK + 1];
     __shared__ __attribute__((aligned(16))) bf16_t b_lds[ALORA_MAX_RANK][FIN_COLS];
 
@@ -58,10 +60,18 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
         if (n >= Nq) sl = slot[t];
     }
     if (adapted) {
-        // S of row i, rank columns c, c+32: hi + lo
+        // S of row i, rank columns c, c+32
         if (t >= 0) {
-            const bf16_t *row = S_hl + (size_t)t * 2 * r;
-            for (int j = c; j < r; j += 32) s_lds[i][j] = bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j]);
+            for (int j = c; j < r; j += 32) {
+                float sj = 0.f;
+                if (s_splits > 1) {
+                    for (int ks = 0; ks < s_splits; ++ks) sj += S_part[((size_t)ks * T + t) * r + j];
+                } else {
+                    const bf16_t *row = (const bf16_t *)S_part + (size_t)t * 2 * r;
+                    sj = bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j]);
+                }
+                s_lds[i][j] = sj;
+            }
         }
         // B[a][:, n0 : n0+256]: rank rows x 32 chunks of 8 features
         const bf16_t *Ba = (const bf16_t *)B.p[a];
@@ -119,7 +129,7 @@ static void launch_finish(const Fwd &f, const PtrTable &B)
 {
     const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
     hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
-                       (const bf16_t *)f.S, B, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
+                       f.S, plan_shrink(f.T, f.H, f.N, f.L).splits, B, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
                        (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
 }
 

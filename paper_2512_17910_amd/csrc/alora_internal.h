@@ -32,7 +32,8 @@ struct Fwd {
     uint8_t *active;
     int8_t *aeff;        // [T] adapter id of adapted rows, -1 for rows that keep the base output
     int32_t *perm, *offsets;
-    void *S;          // bf16: [T,2r] bf16 (hi | lo halves of the fp32 shrink result); f32: [T,r] fp32
+    void *S;          // shrink result.  f32 path: [T][r] fp32.  bf16 path: [T][2r] bf16 (hi | lo halves of the fp32
+                      // result), or with several shrink ranges (see plan_shrink) fp32 partials [ranges][T][r]
     float *partial;      // small-batch path: fp32 partial products [splits][T][N]
     int4 *blocktab;      // shrink: (adapter, first perm index, rows, 0) per 32-row block; adapter -1 = unused
     int n_blocks;        // entries in blocktab (upper bound on 32-row blocks)
@@ -75,5 +76,11 @@ GemmPlan plan_gemm(int T, int H, int N);
 size_t gemm_partial_bytes(int T, int H, int N);
 void set_gemm_tuning(int ntw, int splits);
 int group_blocks(int T, int L);
+constexpr int ALORA_SHRINK_MAX_SPLITS = 8;
+struct ShrinkPlan {
+    int splits;  // ranges of the hidden dimension; the shrink result is the fixed-order sum of their partials
+    int kper;    // width of one range (multiple of 64)
+};
+ShrinkPlan plan_shrink(int T, int H, int N, int L);
 
 }  // namespace alora

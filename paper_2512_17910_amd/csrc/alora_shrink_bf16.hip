@@ -1,19 +1,25 @@
 // LoRA shrink for bf16 batches: S[t,:] = x[t,:] . A[a] for adapted rows only, on bf16 MFMA with
 // fp32 accumulation.  Rows come from the grouped list (adapter-major, stable): a workgroup takes
-// 32 rows of ONE adapter and walks the whole hidden dimension.
+// 32 rows of ONE adapter and one range of the hidden dimension (blockIdx.y).
 //
 // The kernel moves a few MB and is bound by how many bytes one compute unit keeps in flight, so
-// it streams: the hidden dimension is cut into chunks, two LDS buffers alternate, and all loads
-// of a chunk are issued at once as direct-to-LDS copies (the gathered token rows, 16-byte chunks
-// XOR-swizzled by row; the adapter's A rows copied verbatim, they are already k-major) while the
-// previous chunk runs its MFMAs out of LDS (ds_read_b128 for tokens, the transposing
-// ds_read_b64_tr_b16 for A).  The four wavefronts split every chunk's k steps; their partial sums
-// are added in fixed order at the end.
+// it streams: its range is cut into chunks, two LDS buffers alternate, and all loads of a chunk are
+// issued at once as direct-to-LDS copies (the gathered token rows, 16-byte chunks XOR-swizzled by
+// row; the adapter's A rows copied verbatim, they are already k-major) while the previous chunk
+// runs its MFMAs out of LDS (ds_read_b128 for tokens, the transposing ds_read_b64_tr_b16 for A).
+// The four wavefronts split every chunk's k steps; their partial sums are added in fixed order at
+// the end.
 //
-// The fp32 result is handed on as two bf16 numbers per element, S = hi + lo with hi = bf16(S),
-// lo = bf16(S - hi), stored as [hi_0..hi_{r-1} | lo_0..lo_{r-1}] per row: the projection kernel
-// runs the expand on the same bf16 MFMA pipe as the base GEMM ([S_hi | S_lo] against [B ; B])
-// and still sees ~16 mantissa bits of S.
+// Two forms of the result, chosen by the host with the projection's plan:
+//   - one range (prefill-sized batches, enough row blocks to fill the chip): the fp32 result is
+//     handed on as two bf16 numbers per element, S = hi + lo with hi = bf16(S), lo = bf16(S - hi),
+//     stored as [hi_0..hi_{r-1} | lo_0..lo_{r-1}] per row: the projection kernel runs the expand on
+//     the same bf16 MFMA pipe as the base GEMM ([S_hi | S_lo] against [B ; B]) and still sees ~16
+//     mantissa bits of S;
+//   - several ranges (small batches, a handful of row blocks that would each be latency-bound over
+//     the whole hidden dimension): every range leaves an fp32 partial P[range][t][:], and the
+//     finishing kernel adds the ranges in fixed order.
+#include <algorithm>
 #include "alora_internal.h"
 
 namespace alora {
@@ -31,7 +37,7 @@ template <int KSL, int NT>
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restrict__ x, PtrTable A,
                                                           const int32_t *__restrict__ perm,
                                                           const int4 *__restrict__ blocktab, int L, int H, int r, uint32_t x_bytes,
-                                                          bf16_t *__restrict__ S_hl)
+                                                          int T, int kper, void *__restrict__ S_out)
 {
     constexpr int XROW_BYTES = KSL * 2;
     constexpr int CPR = KSL / 8;                 // 16-byte chunks per token row
@@ -51,6 +57,8 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
     const int4 entry = blocktab[blockIdx.x];
     const int a = entry.x, j0 = entry.y, cnt = entry.z;
     if (a < 0 || a >= L) return;  // unused entry or the base group; uniform across the workgroup
+    // this workgroup's range of the hidden dimension (the host sizes gridDim.y so that none is empty)
+    const int kbeg = (int)blockIdx.y * kper, kend = min(H, kbeg + kper);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -84,7 +92,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
         xoff[qq] = t >= 0 ? (uint32_t)t * (uint32_t)H * 2u + 16u * xchunk[qq] : 0xffffffffu;
     }
     auto issue = [&](int ks0, unsigned char *xs, unsigned char *as) {
-        const int klen = min(KSL, H - ks0);  // multiple of 64
+        const int klen = min(KSL, kend - ks0);  // multiple of 64
 #pragma unroll
         for (int qq = 0; qq < AI; ++qq) {
             const int q = w * AI + qq;
@@ -155,19 +163,19 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
 #define SHRINK_WAIT_ALL() asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory")
 #define SHRINK_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
-    const int nchunks = (H + KSL - 1) / KSL;
-    issue(0, xs0, as0);
-    if (nchunks > 1) issue(KSL, xs1, as1);
+    const int nchunks = (kend - kbeg + KSL - 1) / KSL;
+    issue(kbeg, xs0, as0);
+    if (nchunks > 1) issue(kbeg + KSL, xs1, as1);
     for (int i = 0; i < nchunks; i += 2) {
         if (i + 1 < nchunks) SHRINK_WAIT_OLDER(); else SHRINK_WAIT_ALL();
         compute(xs0, as0);
         SHRINK_BARRIER();  // every wavefront is done with buffer 0
-        if (i + 2 < nchunks) issue((i + 2) * KSL, xs0, as0);
+        if (i + 2 < nchunks) issue(kbeg + (i + 2) * KSL, xs0, as0);
         if (i + 1 >= nchunks) break;
         if (i + 2 < nchunks) SHRINK_WAIT_OLDER(); else SHRINK_WAIT_ALL();
         compute(xs1, as1);
         SHRINK_BARRIER();
-        if (i + 3 < nchunks) issue((i + 3) * KSL, xs1, as1);
+        if (i + 3 < nchunks) issue(kbeg + (i + 3) * KSL, xs1, as1);
     }
 #undef SHRINK_WAIT_OLDER
 #undef SHRINK_WAIT_ALL
@@ -182,31 +190,51 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
             for (int jj = 0; jj < 4; ++jj) red[w][nt][8 * g + 4 * lh + jj][li] = acc[nt][4 * g + jj];
     __syncthreads();
 
-    // ---- add the four wavefronts in fixed order, split into (hi, lo), store -----------------------
+    // ---- add the four wavefronts in fixed order; store (hi, lo) or this range's fp32 partial -----
+    const bool ranges = gridDim.y > 1;
     for (int idx = tid; idx < 32 * 32 * NT; idx += 256) {
         const int col = idx % (32 * NT), row = idx / (32 * NT);
         const int tt = rows_t[row];
         if (tt < 0 || col >= r) continue;
         const int nt = col >> 5, c = col & 31;
         const float s = ((red[0][nt][row][c] + red[1][nt][row][c]) + red[2][nt][row][c]) + red[3][nt][row][c];
-        const uint32_t hi = f32_to_bf16_bits(s);
-        const uint32_t lo = f32_to_bf16_bits(s - bf16_bits_to_f32(hi));
-        bf16_t *dst = S_hl + (size_t)tt * 2 * r;
-        dst[col] = (bf16_t)hi;
-        dst[r + col] = (bf16_t)lo;
+        if (ranges) {
+            ((float *)S_out)[((size_t)blockIdx.y * T + tt) * r + col] = s;
+        } else {
+            const uint32_t hi = f32_to_bf16_bits(s);
+            const uint32_t lo = f32_to_bf16_bits(s - bf16_bits_to_f32(hi));
+            bf16_t *dst = (bf16_t *)S_out + (size_t)tt * 2 * r;
+            dst[col] = (bf16_t)hi;
+            dst[r + col] = (bf16_t)lo;
+        }
     }
+}
+
+// Ranges of the hidden dimension the shrink is cut into.  Only the small-batch path (split
+// projection + finishing kernel) uses more than one: about 512 workgroups' worth of row blocks at
+// most, never more than 8 ranges, each a multiple of 64 wide and none empty.
+ShrinkPlan plan_shrink(int T, int H, int N, int L)
+{
+    ShrinkPlan p = {1, H};
+    if (T <= 0 || L <= 0 || plan_gemm(T, H, N).splits == 1) return p;
+    const int want = std::max(1, std::min(ALORA_SHRINK_MAX_SPLITS, 512 / group_blocks(T, L)));
+    const int k64 = H / 64;
+    p.kper = ((k64 + want - 1) / want) * 64;
+    p.splits = (H + p.kper - 1) / p.kper;
+    return p;
 }
 
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;
-    const dim3 grid(f.n_blocks);
+    const ShrinkPlan sp = plan_shrink(f.T, f.H, f.N, f.L);
+    const dim3 grid(f.n_blocks, sp.splits);
     if (f.r <= 32)
         hipLaunchKernelGGL((shrink_bf16_kernel<512, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
-                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), (bf16_t *)f.S);
+                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), f.T, sp.kper, f.S);
     else
         hipLaunchKernelGGL((shrink_bf16_kernel<256, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
-                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), (bf16_t *)f.S);
+                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), f.T, sp.kper, f.S);
     return (int)hipGetLastError();
 }
 
