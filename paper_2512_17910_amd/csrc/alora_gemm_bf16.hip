@@ -36,9 +36,8 @@ namespace alora {
 
 constexpr int BM = 256, BK = 32;
 constexpr int KBLK = 64;     // granularity of the hidden dimension the host plans splits in
-constexpr int WPITCH = 512;  // bytes per k row of the weight tile in LDS (room for 256 features)
 constexpr int GEMM_THREADS = 256;
-constexpr uint32_t STAGE_BYTES = 32768, W_OFF = 16384;
+constexpr uint32_t W_OFF = 16384;      // a stage is the token tile (256 rows x 64 B) followed by the weight tile
 constexpr uint32_t OOR = 0x80000000u;  // buffer offset that is out of range for every descriptor
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -82,11 +81,11 @@ __device__ __forceinline__ void load_lds16(rsrc_t rsrc, uint32_t lds_addr, uint3
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const lds_byte *p) { return (uint32_t)(uintptr_t)p; }
 
-__device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p)
+__device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p, int pitch)
 {
-    // k..k+3 of this lane's feature column, then k+4..k+7 (four rows of 512 bytes further on)
+    // k..k+3 of this lane's feature column, then k+4..k+7 (four weight rows further on)
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * WPITCH));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * pitch));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
@@ -99,12 +98,22 @@ template <int NTW, bool SPLIT>
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B)
 {
     constexpr int BN = 64 * NTW;
-    // separate LDS objects, so that the compiler can tell that reads of one stage do not depend on
-    // the in-flight direct loads into the others
+    // Ring geometry.  128-feature tiles keep weight rows of 256 bytes, which makes a stage 24 KB and
+    // leaves room for six stages instead of four: four slices in flight instead of two, which is
+    // what the small-batch path needs to keep enough of W on its way from HBM.
+    constexpr int WPITCH = NTW == 2 ? 256 : 512;       // bytes per k row of the weight tile in LDS
+    constexpr int NST = NTW == 2 ? 6 : 4;              // stages
+    constexpr uint32_t STAGE_BYTES = W_OFF + BK * WPITCH;
+    constexpr int LPW = WPITCH / 16;                   // lanes (16-byte chunks) per weight row
+    constexpr int RPW = 64 / LPW;                      // weight rows per copy instruction
+    constexpr int NCW = BK / RPW / 4;                  // weight-tile copy instructions per wavefront and slice
+    constexpr int NC = 4 + NCW;                        // copy instructions per wavefront and slice
     __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char stage2[STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char stage3[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char stage4[NST > 4 ? STAGE_BYTES : 16];
+    __shared__ __attribute__((aligned(16))) unsigned char stage5[NST > 4 ? STAGE_BYTES : 16];
     __shared__ int arow[BM];                       // effective adapter per tile row
     __shared__ int present[ALORA_MAX_ADAPTERS];
     __shared__ int plist[ALORA_MAX_ADAPTERS];      // adapters present in this tile, ascending
@@ -114,6 +123,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     lds_byte *const st1 = (lds_byte *)stage1;
     lds_byte *const st2 = (lds_byte *)stage2;
     lds_byte *const st3 = (lds_byte *)stage3;
+    lds_byte *const st[6] = {st0, st1, st2, st3, (lds_byte *)stage4, (lds_byte *)stage5};
+    lds_byte *const st_x = st[NST - 1];   // the stage the expand phase works in
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -170,10 +181,10 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // chunk lane%4, which holds logical chunk (lane%4) ^ swizzle(row)
     auto x_row = [&](int ii, int ln) { return 64 * w + 16 * ii + (ln >> 2); };
     auto x_chunk = [&](int ii, int ln) { return (ln & 3) ^ ((x_row(ii, ln) >> 2) & 3); };
-    // weight tile: instruction jj of wave w fills k rows 8w + 2jj, +1; lane -> row +lane/32, physical
-    // chunk lane%32 holding logical chunk (lane%32) ^ 4*(k%4)
-    auto w_k = [&](int jj, int ln) { return 8 * w + 2 * jj + (ln >> 5); };
-    auto w_chunk = [&](int jj, int ln) { return (ln & 31) ^ ((w_k(jj, ln) & 3) << 2); };
+    // weight tile: instruction jj of wave w fills the RPW k rows from 8w + RPW*jj; lane -> row
+    // +lane/LPW, physical chunk lane%LPW holding logical chunk (lane%LPW) ^ 4*(k%4)
+    auto w_k = [&](int jj, int ln) { return 8 * w + RPW * jj + ln / LPW; };
+    auto w_chunk = [&](int jj, int ln) { return (ln % LPW) ^ ((w_k(jj, ln) & 3) << 2); };
     auto w_col_ok = [&](int jj, int ln) { return (8 * w_chunk(jj, ln) < BN) & (n0 + 8 * w_chunk(jj, ln) < g.N); };
 
     // ---- per-lane LDS read addresses of the MFMA operands ----------------------------------
@@ -204,37 +215,37 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     const rsrc_t rx = make_rsrc(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
     const rsrc_t rw = make_rsrc(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
     const rsrc_t rs = make_rsrc(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
-    uint32_t vxb[4], vwb[4];
+    uint32_t vxb[4], vwb[NCW];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii) vxb[ii] = (uint32_t)(x_row(ii, lane) * g.H + 8 * x_chunk(ii, lane)) * 2;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) vwb[jj] = w_col_ok(jj, lane) ? (uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
+    for (int jj = 0; jj < NCW; ++jj) vwb[jj] = w_col_ok(jj, lane) ? (uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
     const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
     // base K-slices of this workgroup: all of them, or the range of its split
     const int kt0 = SPLIT ? (int)blockIdx.y * g.kps : 0;
     const int KT = SPLIT ? min(g.H / BK, kt0 + g.kps) : g.H / BK;
     const int n_base = KT - kt0;
 
-    // copies of one 32-wide slice: this wavefront's four token-tile (c = 0..3) and four weight-tile
-    // (c = 4..7) instructions
-    auto copy = [&](int c, rsrc_t r_x, const uint32_t (&vx)[4], uint32_t sx, rsrc_t r_w, const uint32_t (&vw)[4],
-                    uint32_t sw, uint32_t st) {
-        if (c < 4) load_lds16(r_x, st + (uint32_t)(64 * w + 16 * c) * (BK * 2), vx[c], sx);
-        else load_lds16(r_w, st + W_OFF + (uint32_t)(8 * w + 2 * (c - 4)) * WPITCH, vw[c - 4], sw);
+    // copies of one 32-wide slice: this wavefront's four token-tile (c = 0..3) and NCW weight-tile
+    // (c = 4..) instructions
+    auto copy = [&](int c, rsrc_t r_x, const uint32_t (&vx)[4], uint32_t sx, rsrc_t r_w, const uint32_t (&vw)[NCW],
+                    uint32_t sw, uint32_t sta) {
+        if (c < 4) load_lds16(r_x, sta + (uint32_t)(64 * w + 16 * c) * (BK * 2), vx[c], sx);
+        else load_lds16(r_w, sta + W_OFF + (uint32_t)(8 * w + RPW * (c - 4)) * WPITCH, vw[c - 4], sw);
     };
     // Base slice s of this workgroup.  Slices past the end repeat the last one: every step issues
     // the same number of copies, which is what the in-order wait counts assume.
-    auto issue_base = [&](int s, uint32_t st) {
+    auto issue_base = [&](int s, uint32_t sta) {
         const int kb = kt0 + min(s, n_base - 1);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) copy(c, rx, vxb, kb * xstep, rw, vwb, kb * wstep, st);
+        for (int c = 0; c < NC; ++c) copy(c, rx, vxb, kb * xstep, rw, vwb, kb * wstep, sta);
     };
 
     // MFMA fragments of one 16-wide k step
     auto read_x = [&](const lds_byte *base, int ks, int b) {
         return *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
     };
-    auto read_w = [&](const lds_byte *base, int ks, int a) { return read_w_frag(base + (waddr[a] + ks * 16 * WPITCH)); };
+    auto read_w = [&](const lds_byte *base, int ks, int a) { return read_w_frag(base + (waddr[a] + ks * 16 * WPITCH), WPITCH); };
     auto load_frags = [&](const lds_byte *base, int ks, bf16x8 (&wf)[NTW], bf16x8 (&xf)[4]) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) xf[b] = read_x(base, ks, b);
@@ -251,14 +262,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     bf16x8 wf0[NTW], xf0[4], wf1[NTW], xf1[4];
 
-    // fill the ring with base slices 0, 1, 2; their latency also covers the expand phase
-    const uint32_t sa0 = lds_addr_of(st0), sa1 = lds_addr_of(st1), sa2 = lds_addr_of(st2), sa3 = lds_addr_of(st3);
-    issue_base(0, sa0);
-    issue_base(1, sa1);
-    issue_base(2, sa2);
+    // fill the ring with the first NST-1 base slices; their latency also covers the expand phase
+    uint32_t sa[6];
+#pragma unroll
+    for (int u = 0; u < 6; ++u) sa[u] = lds_addr_of(st[u]);
+#pragma unroll
+    for (int u = 0; u < NST - 1; ++u) issue_base(u, sa[u]);
 
     // ---- 2. expand first, then select ------------------------------------------------------
-    // One slice at a time through the fourth stage (few slices, not pipelined): 32 k of
+    // One slice at a time through the last stage (few slices, not pipelined): 32 k of
     // [S_hi | S_lo] for the rows of adapter a (zeros elsewhere) against the matching rows of [B_a ; B_a].
     if (!SPLIT && n_exp > 0) {
         for (int e = 0; e < n_exp; ++e) {
@@ -266,7 +278,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             const int a = __builtin_amdgcn_readfirstlane(plist[j]);
             const rsrc_t rb =
                 make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(g.r * g.N - n0) * 2);
-            uint32_t vx[4], vw[4];
+            uint32_t vx[4], vw[NCW];
 #pragma unroll
             for (int ii = 0; ii < 4; ++ii) {
                 const int row = x_row(ii, lane), kk = k0 + 8 * x_chunk(ii, lane);
@@ -274,18 +286,18 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                 vx[ii] = ok ? (uint32_t)(row * g.kx + kk) * 2 : OOR;
             }
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
+            for (int jj = 0; jj < NCW; ++jj) {
                 const int kk = k0 + w_k(jj, lane);
                 const int srow = kk >= g.r ? kk - g.r : kk;   // [B ; B]: the hi and the lo half meet the same rows
                 const bool ok = (kk < g.kx) & w_col_ok(jj, lane);
                 vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
             }
 #pragma unroll
-            for (int c = 0; c < 8; ++c) copy(c, rs, vx, 0, rb, vw, 0, sa3);
+            for (int c = 0; c < NC; ++c) copy(c, rs, vx, 0, rb, vw, 0, sa[NST - 1]);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            load_frags(st3, 0, wf0, xf0);
-            load_frags(st3, 1, wf1, xf1);
+            load_frags(st_x, 0, wf0, xf0);
+            load_frags(st_x, 1, wf1, xf1);
             mfmas(wf0, xf0);
             mfmas(wf1, xf1);
             __syncthreads();
@@ -312,15 +324,16 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     // ---- 3. base GEMM ---------------------------------------------------------------------
     // step s: multiplies slice s (stage cur); fetches the first fragments of slice s+1 (stage nxt);
-    // issues the copies of slice s+3 into the stage that slice s-1 occupied (tgt)
+    // issues the copies of slice s+NST-1 into the stage that slice s-1 occupied (tgt)
     // Within a step the source order is the issue order: behind every MFMA one fragment read for
     // the next 16 k until they are all issued, and one copy behind every third MFMA, which keeps the
     // demand on the vector memory pipe (64 B/clk per CU) uniform.
     auto step = [&](int s, const lds_byte *cur, const lds_byte *nxt, uint32_t tgt) {
-        // this wavefront's copies of slices <= s+1 have landed (the 8 of slice s+2 may be in flight);
-        // behind the barrier that holds for every wavefront, and all of them are done reading tgt
-        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-        const int kb = kt0 + min(s + 3, n_base - 1);
+        // this wavefront's copies of slices <= s+1 have landed (those of slices s+2 .. s+NST-2 may be
+        // in flight); behind the barrier that holds for every wavefront, and all of them are done
+        // reading tgt
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NC * (NST - 3)) : "memory");
+        const int kb = kt0 + min(s + NST - 1, n_base - 1);
         const uint32_t sx = kb * xstep, sw = kb * wstep;
         constexpr int NM = 4 * NTW, CI = NTW == 2 ? 2 : 3;
 #pragma unroll
@@ -342,7 +355,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                     else wf0[u - 4] = read_w(nxt, 0, u - 4);
                 }
             }
-            if (gm % CI == 1 && gm / CI < 8) copy(gm / CI, rx, vxb, sx, rw, vwb, sw, tgt);
+            if (gm % CI == 1 && gm / CI < NC) copy(gm / CI, rx, vxb, sx, rw, vwb, sw, tgt);
         }
         // the same order, spelled out for the instruction scheduler (MFMA, then the LDS reads of its unit)
 #pragma unroll
@@ -356,13 +369,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             }
         }
     };
-    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NC * (NST - 2)) : "memory");
     load_frags(st0, 0, wf0, xf0);
-    for (int s = 0; s < n_base; s += 4) {
-        step(s, st0, st1, sa3);
-        if (s + 1 < n_base) step(s + 1, st1, st2, sa0);
-        if (s + 2 < n_base) step(s + 2, st2, st3, sa1);
-        if (s + 3 < n_base) step(s + 3, st3, st0, sa2);
+    for (int s = 0; s < n_base; s += NST) {
+#pragma unroll
+        for (int u = 0; u < NST; ++u)
+            if (u == 0 || s + u < n_base) step(s + u, st[u], st[(u + 1) % NST], sa[(u + NST - 1) % NST]);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
