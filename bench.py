@@ -38,6 +38,9 @@ def main() -> int:
                     help="distinct copies of W/A/B cycled through (0 = 8 for the decode config, else 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--operands", choices=("gaussian", "constant"), default="gaussian",
+                    help="gaussian: the workload's recipe (default).  constant: x and W overwritten with 1.0, a probe of "
+                         "how far the clock under load depends on operand toggling; not the workload, no parity check")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known size) so that a rocprofv3 --pmc run of this "
                          "command holds a reference dispatch for the FETCH_SIZE / WRITE_SIZE counters")
@@ -56,6 +59,9 @@ def main() -> int:
     ab.lib()  # fail loudly if the HIP library is missing
     w = wl.CONFIGS[args.config]()
     db = DeviceBatch(w, cache_fill=False)
+    if args.operands == "constant":
+        db.x.fill_(1.0)
+        db.W.fill_(1.0)
     rotate = args.rotate or (8 if args.config == 3 else 1)
     copies = [(db.W, db.A, db.B)]
     for _ in range(rotate - 1):
@@ -119,13 +125,14 @@ def main() -> int:
 
     out = {"metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic" if args.operands == "gaussian" else "synthetic, x and W constant 1.0 (clock probe, not the workload)",
            "config": {"workload": w.name, "T": w.T, "hidden": w.hidden, "N": w.N, "n_adapters": w.n_adapters,
                       "rank": w.rank, "active_rows": T_act, "block_size": w.block_size,
                       "weight_copies_rotated": rotate},
            "roofline": roof}
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.operands == "gaussian":
         x, W, A, B = host_operands(w)
         threads = oracle.num_threads()
         probe = wl.sample_rows(w, threads)          # about one row per thread

@@ -2,7 +2,8 @@
 // fp32 accumulation.  Rows come from the grouped list (adapter-major, stable): a workgroup takes
 // 32 rows of ONE adapter and one range of the hidden dimension (blockIdx.y).
 //
-// The kernel moves a few MB and is bound by how many bytes one compute unit keeps in flight, so
+// A workgroup pulls its 32 token rows and the whole of its adapter's A (for its range) through one
+// compute unit's vector memory pipe (64 B/clk), which is what bounds it once the loads overlap; so
 // it streams: its range is cut into chunks, two LDS buffers alternate, and all loads of a chunk are
 // issued at once as direct-to-LDS copies (the gathered token rows, 16-byte chunks XOR-swizzled by
 // row; the adapter's A rows copied verbatim, they are already k-major) while the previous chunk
