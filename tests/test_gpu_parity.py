@@ -88,6 +88,11 @@ def test_every_tiling_matches_the_oracle(tuning, ft, sp):
     _check_full(wl.small_mixed("bf16", seed=5, rank=24, n_adapters=5, hidden=320, n_q_heads=9, head_dim=32,
                                seq_lens=(513, 5)))
     _check_full(wl.small_mixed("bf16", seed=4, rank=64, n_adapters=2, hidden=128, seq_lens=(33, 64, 31)))
+    # fewer 32-wide K-slices than the LDS ring has stages (hidden 64), and a slice count that is no
+    # multiple of the ring depth (hidden 448: 14 slices)
+    _check_full(wl.small_mixed("bf16", seed=11, rank=8, n_adapters=2, hidden=64, seq_lens=(70, 200, 9)))
+    _check_full(wl.small_mixed("bf16", seed=12, rank=32, n_adapters=4, hidden=448, n_q_heads=3, head_dim=64,
+                               seq_lens=(260, 31)))
 
 
 @pytest.mark.parametrize("ft,sp", [(4, 1), (2, 4)], ids=["fused", "split"])
