@@ -135,6 +135,34 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
                       void *hip_stream);
 
 /*
+ * Graph-captured call.  Sec. 3 keeps the activation mask in a tensor of fixed address so that the
+ * model's forward pass stays one captured device graph, and App. A's dummy run builds placeholder
+ * aLoRA metadata only so that the mask is part of that graph.  Here: alora_qkv_graph_create records
+ * ONE alora_qkv_forward with exactly these pointers and sizes into a HIP graph (on a stream of its
+ * own; nothing runs) and hands back the instantiated graph; every alora_qkv_graph_launch replays
+ * the whole call (classification/grouping, shrink, projection, stores) on `hip_stream`.
+ *   - Arguments, layouts and preconditions are those of alora_qkv_forward; T must be > 0.
+ *   - All addresses are baked in: before a launch the caller rewrites the CONTENTS of x,
+ *     token_adapter_ids, dims->token_seg_ids, dims->token_positions, activation_start and
+ *     slot_mapping in place.  A batch with fewer than T rows is padded with rows that have
+ *     token_adapter_ids = -1 and slot_mapping = -1 (any x, any valid segment id): they cost a q_out
+ *     row and touch no cache slot.  The A / B pointer tables are read at creation only.
+ *   - Sizes (dims), block_size, the workspace and the tuning in force at creation are baked in too.
+ *   - Ownership: the caller keeps every buffer alive until the graph is destroyed; the library owns
+ *     the alora_graph object.  Launches of one graph must not overlap (they share the workspace).
+ *   - Errors: statuses of alora_qkv_forward; on error *out is NULL and nothing was enqueued.
+ */
+typedef struct alora_graph alora_graph;
+int alora_qkv_graph_create(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                           const void *W_qkv, const void *const *A, const void *const *B,
+                           void *q_out, void *k_cache, void *v_cache,
+                           const int64_t *slot_mapping, int32_t block_size,
+                           const alora_dims *dims, void *workspace, size_t workspace_bytes,
+                           alora_graph **out);
+int alora_qkv_graph_launch(alora_graph *graph, void *hip_stream);
+int alora_qkv_graph_destroy(alora_graph *graph);
+
+/*
  * Slow, synchronous check of the data preconditions listed at the top (copies the index
  * arrays to the host).  Returns ALORA_OK, ALORA_EDATA, or another status for bad arguments.
  * Writes no device memory.

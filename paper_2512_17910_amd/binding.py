@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                         ctypes.POINTER(AloraDims), vp, sz, vp]
         L.alora_qkv_validate.argtypes = [vp, vp, vp, i32, ctypes.POINTER(AloraDims)]
+        L.alora_qkv_graph_create.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                             ctypes.POINTER(AloraDims), vp, sz, ctypes.POINTER(vp)]
+        L.alora_qkv_graph_launch.argtypes = [vp, vp]
+        L.alora_qkv_graph_destroy.argtypes = [vp]
         L.alora_status_string.argtypes = [ctypes.c_int]
         L.alora_status_string.restype = ctypes.c_char_p
         L.alora_qkv_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
@@ -66,7 +70,8 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_profile_begin.argtypes = [ctypes.c_int]
         L.alora_qkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
-                     "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version"):
+                     "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version",
+                     "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -159,6 +164,33 @@ def alora_qkv_forward(x, token_adapter_ids, activation_start, W_qkv, A: Sequence
                                 workspace.numel() if workspace is not None else 0, _stream_handle(stream))
     if s:
         raise AloraError(s, "alora_qkv_forward")
+
+
+def alora_qkv_graph_create(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
+                           q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims, workspace):
+    """Record one forward call with these buffers into a HIP graph; returns an opaque handle for
+    alora_qkv_graph_launch / alora_qkv_graph_destroy.  The caller keeps every tensor alive and rewrites
+    their contents in place between launches."""
+    h = ctypes.c_void_p(None)
+    s = lib().alora_qkv_graph_create(_ptr(x), _ptr(token_adapter_ids), _ptr(activation_start), _ptr(W_qkv),
+                                     _ptr_array(A), _ptr_array(B), _ptr(q_out), _ptr(k_cache), _ptr(v_cache),
+                                     _ptr(slot_mapping), block_size, ctypes.byref(dims), _ptr(workspace),
+                                     workspace.numel() if workspace is not None else 0, ctypes.byref(h))
+    if s:
+        raise AloraError(s, "alora_qkv_graph_create")
+    return h
+
+
+def alora_qkv_graph_launch(graph, stream=None) -> None:
+    s = lib().alora_qkv_graph_launch(graph, _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_qkv_graph_launch")
+
+
+def alora_qkv_graph_destroy(graph) -> None:
+    s = lib().alora_qkv_graph_destroy(graph)
+    if s:
+        raise AloraError(s, "alora_qkv_graph_destroy")
 
 
 def alora_qkv_validate(token_adapter_ids, activation_start, slot_mapping, block_size: int, dims: AloraDims) -> int:

@@ -156,10 +156,12 @@ int alora_qkv_classify_group(const int32_t *token_adapter_ids, const int32_t *ac
     return ALORA_OK;
 }
 
-int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+// Argument checks and the launch sequence of one forward call.  `allow_timing`: the benchmark's
+// event pairs may be recorded (never while the stream is being captured).
+static int forward_on(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
                       const void *W_qkv, const void *const *A, const void *const *B, void *q_out, void *k_cache,
                       void *v_cache, const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims,
-                      void *workspace, size_t workspace_bytes, void *hip_stream)
+                      void *workspace, size_t workspace_bytes, void *hip_stream, bool allow_timing)
 {
     int s = check_dims(dims);
     if (s) return s;
@@ -195,7 +197,7 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
     f.x = x; f.W = W_qkv; f.aid = token_adapter_ids; f.start = activation_start; f.slot = slot_mapping;
     f.q = q_out; f.kc = k_cache; f.vc = v_cache;
 
-    const bool timed = g_prof.on && g_prof.used < (int)g_prof.ev0.size();
+    const bool timed = allow_timing && g_prof.on && g_prof.used < (int)g_prof.ev0.size();
     int e = launch_classify_group(f);
     if (!e) {
         if (f.dtype == ALORA_F32) {
@@ -213,6 +215,73 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
         if (!e && timed) g_prof.used++;
     }
     if (e) { g_last_hip_error = e; return ALORA_EHIP; }
+    return ALORA_OK;
+}
+
+int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                      const void *W_qkv, const void *const *A, const void *const *B, void *q_out, void *k_cache,
+                      void *v_cache, const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return forward_on(x, token_adapter_ids, activation_start, W_qkv, A, B, q_out, k_cache, v_cache, slot_mapping,
+                      block_size, dims, workspace, workspace_bytes, hip_stream, true);
+}
+
+struct alora_graph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+int alora_qkv_graph_create(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                           const void *W_qkv, const void *const *A, const void *const *B, void *q_out,
+                           void *k_cache, void *v_cache, const int64_t *slot_mapping, int32_t block_size,
+                           const alora_dims *dims, void *workspace, size_t workspace_bytes, alora_graph **out)
+{
+    if (!out) return ALORA_EINVAL;
+    *out = nullptr;
+    if (!dims || dims->T <= 0) return ALORA_EINVAL;
+    hipStream_t cs = nullptr;
+    hipError_t e = hipStreamCreateWithFlags(&cs, hipStreamNonBlocking);
+    if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+    e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
+    if (e) { (void)hipStreamDestroy(cs); g_last_hip_error = (int)e; return ALORA_EHIP; }
+    // argument errors are found before anything is enqueued; the capture is ended either way
+    const int status = forward_on(x, token_adapter_ids, activation_start, W_qkv, A, B, q_out, k_cache, v_cache,
+                                  slot_mapping, block_size, dims, workspace, workspace_bytes, cs, false);
+    hipGraph_t graph = nullptr;
+    e = hipStreamEndCapture(cs, &graph);
+    (void)hipStreamDestroy(cs);
+    if (status != ALORA_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return status;
+    }
+    if (e || !graph) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e) { (void)hipGraphDestroy(graph); g_last_hip_error = (int)e; return ALORA_EHIP; }
+    alora_graph *g = new alora_graph;
+    g->graph = graph;
+    g->exec = exec;
+    *out = g;
+    return ALORA_OK;
+}
+
+int alora_qkv_graph_launch(alora_graph *graph, void *hip_stream)
+{
+    if (!graph || !graph->exec) return ALORA_EINVAL;
+    const hipError_t e = hipGraphLaunch(graph->exec, (hipStream_t)hip_stream);
+    if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+    return ALORA_OK;
+}
+
+int alora_qkv_graph_destroy(alora_graph *graph)
+{
+    if (!graph) return ALORA_OK;
+    hipError_t e = hipSuccess;
+    if (graph->exec) e = hipGraphExecDestroy(graph->exec);
+    if (graph->graph) { const hipError_t e2 = hipGraphDestroy(graph->graph); if (!e) e = e2; }
+    delete graph;
+    if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
     return ALORA_OK;
 }
 
