@@ -112,6 +112,7 @@ const char *alora_status_string(int s)
     case ALORA_EWORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case ALORA_EHIP: return "a HIP call failed (see alora_last_hip_error)";
     case ALORA_EDATA: return "device data violates a documented precondition";
+    case -7: return "not enough free cache blocks (planner)";
     default: return "unknown status";
     }
 }

@@ -1,4 +1,4 @@
-"""The C-ABI library loads, exports every symbol include/alora_qkv.h declares, and its host-side
+"""The C-ABI library loads, exports every symbol the headers under include/ declare, and its host-side
 argument checks answer without touching a GPU (no compute call is made here)."""
 import ctypes
 import os
@@ -13,15 +13,21 @@ HEADER = os.path.join(ROOT, "include", "alora_qkv.h")
 
 
 def _declared_functions():
-    src = open(HEADER).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(alora_[a-z_]+)\s*\(", src)))
+    """Every function declared in any header under include/."""
+    import glob
+    names = set()
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        src = open(h).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(alora_[a-z_]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"alora_qkv_forward", "alora_qkv_workspace_bytes", "alora_qkv_classify_group",
-            "alora_qkv_validate", "alora_status_string"} <= set(names)
+            "alora_qkv_validate", "alora_status_string", "alora_qkv_graph_create", "alora_planner_admit",
+            "alora_planner_commit"} <= set(names)
     L = ab.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"
