@@ -223,3 +223,29 @@ def test_validate_reports_bad_data():
     assert db.validate() == ab.ALORA_OK
     db.aid[0] = w.n_adapters
     assert db.validate() == ab.ALORA_EDATA
+
+
+def _random_shape(rng, dtype):
+    """A seeded random small batch: odd head counts and dims, ragged lengths, padding rows."""
+    if dtype == "bf16":
+        hidden = 64 * int(rng.integers(1, 9))
+        head_dim = 8 * int(rng.integers(1, 17))
+        rank = 8 * int(rng.integers(1, 9))
+    else:
+        hidden = 4 * int(rng.integers(4, 80))
+        head_dim = 4 * int(rng.integers(1, 20))
+        rank = int(rng.integers(1, 65))
+    n_seq = int(rng.integers(1, 7))
+    return dict(dtype=dtype, hidden=hidden, head_dim=head_dim, n_q_heads=int(rng.integers(1, 8)),
+                n_kv_heads=int(rng.integers(1, 4)), n_adapters=int(rng.integers(1, 12)), rank=rank,
+                seq_lens=tuple(int(rng.integers(1, 400)) for _ in range(n_seq)),
+                pad_every=int(rng.choice([0, 3, 11])), seed=int(rng.integers(1, 1 << 20)))
+
+
+@pytest.mark.parametrize("dtype,n_cases", [("bf16", 14), ("f32", 6)])
+def test_random_shapes_match_the_oracle(dtype, n_cases):
+    rng = np.random.default_rng(20250 + len(dtype))
+    for _ in range(n_cases):
+        kw = _random_shape(rng, dtype)
+        print(f"[shape] {kw}", flush=True)
+        _check_full(wl.small_mixed(**kw))
