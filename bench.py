@@ -104,6 +104,14 @@ def main() -> int:
     gemm_ms, n_meas = ab.alora_qkv_profile_end()
     if n_meas == 0:   # graph replays carry no in-call events
         gemm_ms = float("nan")
+    # spread of single steps: HIP events on the launch stream around each of 50 further steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        step(i)
+        e1.record()
+    torch.cuda.synchronize()
+    per_step_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = w.T * args.steps / (t1 - t0)
 
@@ -149,8 +157,14 @@ def main() -> int:
                       "rank": w.rank, "active_rows": T_act, "block_size": w.block_size,
                       "weight_copies_rotated": rotate, "hip_graph": bool(graphs)},
            "host_enqueue_us_per_step": (t_enq - t0) * 1e6 / args.steps,
+           "step_us_median": per_step_us[len(per_step_us) // 2], "step_us_min": per_step_us[0],
            "roofline": roof}
 
+    if args.config == 5:
+        # context, not the metric: the rate if the cached, skipped prefix tokens were counted as served
+        served = sum(s.first_pos + s.n_tokens for s in w.segments
+                     if s is max((u for u in w.segments if u.seq == s.seq), key=lambda u: u.first_pos))
+        out["effective_tokens_per_s_counting_cached_prefix"] = served * args.steps / (t1 - t0)
     if not args.no_cpu_baseline and args.operands == "gaussian":
         x, W, A, B = host_operands(w)
         threads = oracle.num_threads()
