@@ -147,32 +147,19 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     const int li = lane & 31, lh = lane >> 5;
     const int rows_valid = min(g.T - m0, BM);
 
-    // ---- 1. this tile's rows: effective adapter (from the grouping kernel), cache slot; adapters present
-    int n_exp = 0;           // expand slices ahead of the base slices
-    int epa = 0;             // expand slices per adapter
-    {
-        const int t = m0 + tid;
-        int a = -1;
-        if (!SPLIT && t < g.T && g.L > 0) a = g.aeff[t];
-        slot_lds[tid] = (!SPLIT && t < g.T) ? g.slot[t] : -1;
-        arow[tid] = a;
-        if (tid < ALORA_MAX_ADAPTERS) present[tid] = 0;
-        __syncthreads();
-        if (a >= 0) present[a] = 1;
-        __syncthreads();
-        if (tid < 64) {
-            const bool p0 = present[tid] != 0, p1 = present[64 + tid] != 0;
-            const uint64_t b0 = __ballot(p0), b1 = __ballot(p1);
-            const uint64_t below = (1ull << tid) - 1ull;
-            const int c0 = __popcll(b0);
-            if (p0) plist[__popcll(b0 & below)] = tid;
-            if (p1) plist[c0 + __popcll(b1 & below)] = 64 + tid;
-            if (tid == 0) n_present = c0 + __popcll(b1);
-        }
-        __syncthreads();
-        if (!SPLIT) {
-            epa = (g.kx + BK - 1) / BK;
-            n_exp = __builtin_amdgcn_readfirstlane(n_present) * epa;
+    // ---- 1. this tile's rows: effective adapter (from the grouping kernel) and cache slot ------
+    // The two loads are issued here and waited for only after the ring has been filled (loads
+    // complete in order, so "all but the ring's copies" means these two have arrived).  They are
+    // assembly statements for the reason given at load_lds16: a wait the compiler places for them
+    // would also wait for every copy issued in between.
+    int a_row = -1;
+    int64_t slot_row = -1;
+    if (!SPLIT && m0 + tid < g.T) {
+        const int64_t *ps = g.slot + (m0 + tid);
+        asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(slot_row) : "v"(ps) : "memory");
+        if (g.L > 0) {
+            const int8_t *pa = g.aeff + (m0 + tid);
+            asm volatile("global_load_sbyte %0, %1, off" : "=v"(a_row) : "v"(pa) : "memory");
         }
     }
 
@@ -268,6 +255,31 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     for (int u = 0; u < 6; ++u) sa[u] = lds_addr_of(st[u]);
 #pragma unroll
     for (int u = 0; u < NST - 1; ++u) issue_base(u, sa[u]);
+
+    // the tile's rows have arrived (only the ring's copies may still be in flight): adapters present
+    int n_exp = 0;           // expand slices ahead of the base slices
+    int epa = 0;             // expand slices per adapter
+    if (!SPLIT) {
+        asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a_row), "+v"(slot_row) : "n"(NC * (NST - 1)) : "memory");
+        slot_lds[tid] = slot_row;
+        arow[tid] = a_row;
+        if (tid < ALORA_MAX_ADAPTERS) present[tid] = 0;
+        __syncthreads();
+        if (a_row >= 0) present[a_row] = 1;
+        __syncthreads();
+        if (tid < 64) {
+            const bool p0 = present[tid] != 0, p1 = present[64 + tid] != 0;
+            const uint64_t b0 = __ballot(p0), b1 = __ballot(p1);
+            const uint64_t below = (1ull << tid) - 1ull;
+            const int c0 = __popcll(b0);
+            if (p0) plist[__popcll(b0 & below)] = tid;
+            if (p1) plist[c0 + __popcll(b1 & below)] = 64 + tid;
+            if (tid == 0) n_present = c0 + __popcll(b1);
+        }
+        __syncthreads();
+        epa = (g.kx + BK - 1) / BK;
+        n_exp = __builtin_amdgcn_readfirstlane(n_present) * epa;
+    }
 
     // ---- 2. expand first, then select ------------------------------------------------------
     // One slice at a time through the last stage (few slices, not pipelined): 32 k of
