@@ -19,7 +19,7 @@ static Profile g_prof;
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t active, aeff, perm, offsets, S, blocktab, partial, total;
+    size_t active, aeff, perm, offsets, S, blocktab, hist, partial, total;
     int n_blocks;
 };
 
@@ -60,6 +60,7 @@ static Layout make_layout(const alora_dims *d)
     l.S = o;       o += up256(T * r * 4 * (d->dtype == ALORA_BF16 ? (size_t)ALORA_SHRINK_MAX_SPLITS : 1));
     l.n_blocks = group_blocks(d->T, d->n_adapters);
     l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
+    l.hist = o;     o += up256(group_hist_bytes(d->T));
     l.partial = o;
     if (d->dtype == ALORA_BF16) o += up256(gemm_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
     l.total = std::max<size_t>(o, 256);
@@ -88,6 +89,7 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
     f.offsets = (int32_t *)(b + l.offsets);
     f.S = b + l.S;
     f.blocktab = (int4 *)(b + l.blocktab);
+    f.hist = (int32_t *)(b + l.hist);
     f.partial = (float *)(b + l.partial);
     f.n_blocks = l.n_blocks;
     f.stream = (hipStream_t)stream;

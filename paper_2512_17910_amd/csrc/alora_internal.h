@@ -35,6 +35,7 @@ struct Fwd {
     void *S;          // shrink result.  f32 path: [T][r] fp32.  bf16 path: [T][2r] bf16 (hi | lo halves of the fp32
                       // result), or with several shrink ranges (see plan_shrink) fp32 partials [ranges][T][r]
     float *partial;      // small-batch path: fp32 partial products [splits][T][N]
+    int32_t *hist;       // large batches: rows per (2048-row slice, group), see the grouping kernels
     int4 *blocktab;      // shrink: (adapter, first perm index, rows, 0) per 32-row block; adapter -1 = unused
     int n_blocks;        // entries in blocktab (upper bound on 32-row blocks)
     hipStream_t stream;
@@ -76,6 +77,7 @@ GemmPlan plan_gemm(int T, int H, int N);
 size_t gemm_partial_bytes(int T, int H, int N);
 void set_gemm_tuning(int ntw, int splits);
 int group_blocks(int T, int L);
+size_t group_hist_bytes(int T);
 constexpr int ALORA_SHRINK_MAX_SPLITS = 8;
 struct ShrinkPlan {
     int splits;  // ranges of the hidden dimension; the shrink result is the fixed-order sum of their partials

@@ -10,8 +10,8 @@
 // the original row order and the grouping is stable without any sort: count per (wavefront,
 // group), prefix-sum the counts group-major / wavefront-minor, then place rows with
 // wavefront-local cursors.  Ranks inside a 64-row step come from ballots, so there are no
-// data-dependent atomics and the result is deterministic.  Batches too large for the LDS row
-// cache re-classify from global memory in both sweeps.
+// data-dependent atomics and the result is deterministic.  Batches of 6144 rows or more take the
+// two-launch, many-workgroup form further down.
 #include "alora_internal.h"
 
 namespace alora {
@@ -182,17 +182,205 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     }
 }
 
+// ---- large batches: the same result from two launches of many workgroups -----------------------
+// Above a few thousand rows the single workgroup is the longest pole in front of the shrink, so
+// the rows are cut into slices of PREP_SLICE rows, one workgroup each.  Launch 1 classifies its
+// slice (App. B mask) and leaves the slice's row count per group in hist[slice][group].  Launch 2
+// turns the histogram into positions: group offsets (totals over all slices), the base of this
+// slice inside every group (totals of the slices before it), then the same wavefront-local
+// placement as above.  "Slice, then wavefront, then row" is the original row order: stable, no
+// sort, no data-dependent atomics, bit-identical to the single-workgroup kernel.
+constexpr int PREP_SLICE = 2048;                      // rows per workgroup: 128 per wavefront
+constexpr int PREP_SLICE_PER_WAVE = PREP_SLICE / PREP_WAVES;
+
+__device__ __forceinline__ unsigned long long same_key_lanes_of(int key_l, int key_bits)
+{
+    unsigned long long same = __ballot(key_l >= 0);
+    for (int bit = 0; bit < key_bits; ++bit) {
+        const bool mine = (key_l >> bit) & 1;
+        const unsigned long long b = __ballot(mine);
+        same &= mine ? b : ~b;
+    }
+    return key_l >= 0 ? same : 0ull;
+}
+
+// per-(wavefront, group) row counts of this slice out of the slice's adapter bytes in LDS
+__device__ __forceinline__ void slice_counts(const int8_t *aeff_s, int rows, int L, int key_bits, int *my_cnt, int w,
+                                             int lane)
+{
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+    for (int tb = w * PREP_SLICE_PER_WAVE; tb < min(rows, (w + 1) * PREP_SLICE_PER_WAVE); tb += 64) {
+        const int i = tb + lane;
+        const int key_l = i < min(rows, (w + 1) * PREP_SLICE_PER_WAVE) ? (aeff_s[i] >= 0 ? aeff_s[i] : L) : -1;
+        const unsigned long long same = same_key_lanes_of(key_l, key_bits);
+        if (same && !(same & lanes_below)) atomicAdd(&my_cnt[key_l], __popcll(same));
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+__global__ __launch_bounds__(PREP_THREADS) void classify_slices_kernel(
+    const int32_t *__restrict__ aid, const int32_t *__restrict__ seg, const int32_t *__restrict__ pos,
+    const int32_t *__restrict__ start, int T, int L, uint8_t *__restrict__ active, int8_t *__restrict__ aeff_out,
+    int32_t *__restrict__ hist)
+{
+    __shared__ int cnt[PREP_WAVES][NKEYS];
+    __shared__ int8_t aeff_s[PREP_SLICE];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r0 = (int)blockIdx.x * PREP_SLICE, rows = min(T - r0, PREP_SLICE);
+    for (int i = threadIdx.x; i < PREP_WAVES * NKEYS; i += PREP_THREADS) (&cnt[0][0])[i] = 0;
+    // classification: two independent rows per thread, the dependent loads paid once
+    constexpr int U = PREP_SLICE / PREP_THREADS;
+    int a[U], s[U], p[U], st[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = threadIdx.x + u * PREP_THREADS;
+        a[u] = i < rows ? aid[r0 + i] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = threadIdx.x + u * PREP_THREADS;
+        s[u] = a[u] >= 0 ? seg[r0 + i] : 0;
+        p[u] = a[u] >= 0 ? pos[r0 + i] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) st[u] = a[u] >= 0 ? start[s[u]] : 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = threadIdx.x + u * PREP_THREADS;
+        if (i < rows) {
+            const int e = (a[u] >= 0 && p[u] >= st[u]) ? a[u] : -1;
+            aeff_s[i] = (int8_t)e;
+            aeff_out[r0 + i] = (int8_t)e;
+            active[r0 + i] = (uint8_t)(e >= 0);
+        }
+    }
+    __syncthreads();
+    slice_counts(aeff_s, rows, L, 32 - __clz(L | 1), cnt[w], w, lane);
+    __syncthreads();
+    if ((int)threadIdx.x <= L) {
+        int run = 0;
+        for (int ww = 0; ww < PREP_WAVES; ++ww) run += cnt[ww][threadIdx.x];
+        hist[(size_t)blockIdx.x * NKEYS + threadIdx.x] = run;
+    }
+}
+
+__global__ __launch_bounds__(PREP_THREADS) void place_slices_kernel(
+    const int8_t *__restrict__ aeff_in, const int32_t *__restrict__ hist, int T, int L, int32_t *__restrict__ perm,
+    int32_t *__restrict__ offsets, int4 *__restrict__ blocktab, int n_blocks)
+{
+    __shared__ int cnt[PREP_WAVES][NKEYS];
+    __shared__ int goff[3 * 64 + 1], bfirst[3 * 64 + 1], tot[3 * 64], slice_base[NKEYS];
+    __shared__ int8_t aeff_s[PREP_SLICE];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r0 = (int)blockIdx.x * PREP_SLICE, rows = min(T - r0, PREP_SLICE);
+    const int key_bits = 32 - __clz(L | 1);
+    for (int i = threadIdx.x; i < PREP_WAVES * NKEYS; i += PREP_THREADS) (&cnt[0][0])[i] = 0;
+    if (threadIdx.x < 3 * 64) tot[threadIdx.x] = 0;
+    for (int i = threadIdx.x; i < rows; i += PREP_THREADS) aeff_s[i] = aeff_in[r0 + i];
+    __syncthreads();
+    slice_counts(aeff_s, rows, L, key_bits, cnt[w], w, lane);
+    // group totals over all slices, and the rows of earlier slices in every group
+    if ((int)threadIdx.x <= L) {
+        int before = 0, all = 0;
+        for (int sl = 0; sl < (int)gridDim.x; ++sl) {
+            const int c = hist[(size_t)sl * NKEYS + threadIdx.x];
+            if (sl < (int)blockIdx.x) before += c;
+            all += c;
+        }
+        slice_base[threadIdx.x] = before;
+        tot[threadIdx.x] = all;
+    }
+    __syncthreads();
+    // exclusive prefix over wavefronts inside each group
+    if ((int)threadIdx.x <= L) {
+        int run = 0;
+        for (int ww = 0; ww < PREP_WAVES; ++ww) {
+            const int c = cnt[ww][threadIdx.x];
+            cnt[ww][threadIdx.x] = run;
+            run += c;
+        }
+    }
+    // one wavefront scans the group totals (three groups per lane): row offsets of the groups and
+    // first 32-row block of every group in the block table
+    if (w == 0) {
+        int c[3], b[3], nrows = 0, blks = 0;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            c[u] = tot[3 * lane + u];
+            b[u] = (c[u] + 31) >> 5;
+            nrows += c[u];
+            blks += b[u];
+        }
+        const int my_rows = nrows, my_blks = blks;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int r_up = __shfl_up(nrows, d), b_up = __shfl_up(blks, d);
+            if (lane >= d) { nrows += r_up; blks += b_up; }
+        }
+        int ro = nrows - my_rows, bo = blks - my_blks;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            goff[3 * lane + u] = ro;
+            bfirst[3 * lane + u] = bo;
+            ro += c[u];
+            bo += b[u];
+        }
+        if (lane == 63) { goff[3 * 64] = nrows; bfirst[3 * 64] = blks; }
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if ((int)threadIdx.x <= L + 1) offsets[threadIdx.x] = goff[threadIdx.x];
+    }
+    // block table, its entries dealt round-robin to the workgroups
+    for (int e = (int)blockIdx.x * PREP_THREADS + threadIdx.x; e < n_blocks; e += (int)gridDim.x * PREP_THREADS) {
+        int4 v = make_int4(-1, 0, 0, 0);
+        if (e < bfirst[3 * 64]) {
+            int lo = 0, hi = L;  // smallest group whose blocks end after e
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (bfirst[mid + 1] > e) hi = mid; else lo = mid + 1;
+            }
+            const int b = e - bfirst[lo];
+            v = make_int4(lo, goff[lo] + 32 * b, min(32, tot[lo] - 32 * b), 0);
+        }
+        blocktab[e] = v;
+    }
+    // placement
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+    int *my_cnt = cnt[w];
+    const int w_end = min(rows, (w + 1) * PREP_SLICE_PER_WAVE);
+    for (int tb = w * PREP_SLICE_PER_WAVE; tb < w_end; tb += 64) {
+        const int i = tb + lane;
+        const int key_l = i < w_end ? (aeff_s[i] >= 0 ? aeff_s[i] : L) : -1;
+        const unsigned long long same = same_key_lanes_of(key_l, key_bits);
+        // every lane reads its group's cursor before the group's first lane advances it
+        if (same) perm[goff[key_l] + slice_base[key_l] + my_cnt[key_l] + __popcll(same & lanes_below)] = r0 + i;
+        __builtin_amdgcn_wave_barrier();
+        if (same && !(same & lanes_below)) atomicAdd(&my_cnt[key_l], __popcll(same));
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 int group_blocks(int T, int L) { return (T + 31) / 32 + L + 1; }
+
+// rows from which the two-launch grouping is used, and the bytes of its histogram
+constexpr int PREP_TWO_LAUNCH_FROM = 6144;
+size_t group_hist_bytes(int T) { return T >= PREP_TWO_LAUNCH_FROM ? (size_t)((T + PREP_SLICE - 1) / PREP_SLICE) * NKEYS * 4 : 0; }
 
 int launch_classify_group(const Fwd &f)
 {
     if (f.T == 0) return 0;
-    if (f.T <= PREP_CACHE_ROWS)
-        hipLaunchKernelGGL(classify_group_kernel<true>, dim3(1), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg, f.pos,
-                           f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks);
-    else
-        hipLaunchKernelGGL(classify_group_kernel<false>, dim3(1), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg,
-                           f.pos, f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks);
+    if (f.T >= PREP_TWO_LAUNCH_FROM) {
+        const int slices = (f.T + PREP_SLICE - 1) / PREP_SLICE;
+        hipLaunchKernelGGL(classify_slices_kernel, dim3(slices), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg, f.pos,
+                           f.start, f.T, f.L, f.active, f.aeff, f.hist);
+        hipLaunchKernelGGL(place_slices_kernel, dim3(slices), dim3(PREP_THREADS), 0, f.stream, (const int8_t *)f.aeff,
+                           (const int32_t *)f.hist, f.T, f.L, f.perm, f.offsets, f.blocktab, f.n_blocks);
+        return (int)hipGetLastError();
+    }
+    static_assert(PREP_TWO_LAUNCH_FROM <= PREP_CACHE_ROWS, "smaller batches fit the single workgroup's LDS row cache");
+    hipLaunchKernelGGL(classify_group_kernel<true>, dim3(1), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg, f.pos,
+                       f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks);
     return (int)hipGetLastError();
 }
 

@@ -196,7 +196,9 @@ def test_empty_batch_is_a_noop(dtype):
 def test_classify_group_large_random():
     """Grouping alone on batches far larger than one tile, up to the adapter limit."""
     rng = np.random.default_rng(4)
-    for T, L, G in ((1, 1, 1), (63, 2, 3), (5000, 128, 40), (26176, 32, 12)):
+    # 6144 rows is where the grouping switches from one workgroup to 2048-row slices over two launches
+    for T, L, G in ((1, 1, 1), (63, 2, 3), (5000, 128, 40), (6143, 7, 5), (6144, 7, 5), (6145, 1, 2), (8193, 128, 9),
+                    (26176, 32, 12), (100001, 3, 50)):
         aid = rng.integers(-1, L, size=T).astype(np.int32)
         seg = rng.integers(0, G, size=T).astype(np.int32)
         pos = rng.integers(0, 50, size=T).astype(np.int32)
