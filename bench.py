@@ -25,7 +25,7 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 METRIC = "masked-aLoRA QKV tokens/s at 1 MI355X; % bf16 MFMA peak / % HBM GB/s"
-BOUND = {2: "mfma", 3: "hbm", 4: "mfma", 5: "mfma"}
+BOUND = {2: "mfma", 3: "hbm", 4: "mfma", 5: "mfma", 6: "mfma"}
 
 
 def main() -> int:
@@ -33,7 +33,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5))
+    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5, 6))
     ap.add_argument("--rotate", type=int, default=0,
                     help="distinct copies of W/A/B cycled through (0 = 8 for the decode config, else 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -80,6 +80,10 @@ def main() -> int:
             ab.alora_qkv_graph_launch(graphs[i % rotate])
             return
         W, A, B = copies[i % rotate]
+        if db.bias is not None or w.adapter_ranks is not None:   # adapter-layout variants (config 6)
+            ab.alora_qkv_forward_ex(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot,
+                                    w.block_size, db.dims, db.ws, bias=db.bias, adapter_ranks=w.adapter_ranks)
+            return
         ab.alora_qkv_forward(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot,
                              w.block_size, db.dims, db.ws)
 
@@ -121,7 +125,9 @@ def main() -> int:
     used = len(set(int(a) for a in w.token_adapter_ids[act == 1]))
     T_w = int((w.slot_mapping >= 0).sum())
     e = w.elem_bytes
-    flops = 2.0 * w.T * w.hidden * w.N + 2.0 * T_act * w.rank * w.N
+    rk = w.adapter_ranks or [w.rank] * w.n_adapters
+    act_rank = float(sum(rk[int(a)] for a in w.token_adapter_ids[act == 1]))   # sum of the active rows' ranks
+    flops = 2.0 * w.T * w.hidden * w.N + 2.0 * act_rank * w.N
     if args.config == 3:
         # small-batch path: the dominant kernel is the split projection, which streams x and W;
         # adapters, rounding and the stores belong to the finishing kernel
@@ -170,12 +176,13 @@ def main() -> int:
         threads = oracle.num_threads()
         probe = wl.sample_rows(w, threads)          # about one row per thread
         tp = time.perf_counter()
-        oracle.alora_rows(x, W, A, B, w.token_adapter_ids, act, probe)
+        bias64 = wl.widen_f64(w.bias, w.dtype) if w.bias is not None else None
+        oracle.alora_rows_var(x, W, A, B, w.token_adapter_ids, act, probe, bias64)
         row_time = (time.perf_counter() - tp) / max(1, -(-len(probe) // threads))
         n = int(max(threads, min(w.T, args.cpu_seconds * threads / max(row_time, 1e-9))))
         rows = wl.sample_rows(w, n)
         tc = time.perf_counter()
-        y = oracle.alora_rows(x, W, A, B, w.token_adapter_ids, act, rows)
+        y = oracle.alora_rows_var(x, W, A, B, w.token_adapter_ids, act, rows, bias64)
         secs = time.perf_counter() - tc
         out["cpu_baseline"] = {"value": len(rows) / secs, "unit": "tokens/s", "cores": min(threads, len(rows)),
                                "kind": "oracle", "seconds": secs,

@@ -135,6 +135,31 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
                       void *hip_stream);
 
 /*
+ * Adapter-layout variants the paper names, on top of alora_qkv_forward (which is this call with
+ * extras = NULL):
+ *   bias           Algorithm 1 computes the base output as l.apply(x, b): a bias row b [N] (device,
+ *                  dtype of x, 16-byte aligned) is added to the base output of EVERY row, adapted or
+ *                  not, in fp32 before the single rounding.  NULL = no bias.
+ *   adapter_ranks  Sec. 4.1 serves LoRAs of rank 8 beside aLoRAs of rank 32: HOST array
+ *                  [n_adapters]; adapter i has A[i] of shape [hidden, adapter_ranks[i]] and B[i] of
+ *                  shape [adapter_ranks[i], N], 1 <= adapter_ranks[i] <= dims->rank (bf16: multiples
+ *                  of 8), else ALORA_ESHAPE.  NULL = every adapter has rank dims->rank.  Read during
+ *                  the call only.
+ * Per-module factors (separate A^Q, A^K, A^V with B^Q, B^K, B^V; Sec. 2.3) are the block-structured
+ * special case: A = [A^Q | A^K | A^V] of rank 3r and B with B^Q, B^K, B^V on its block diagonal.
+ */
+typedef struct alora_extras {
+    const void *bias;
+    const int32_t *adapter_ranks;
+} alora_extras;
+int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                         const void *W_qkv, const void *const *A, const void *const *B,
+                         void *q_out, void *k_cache, void *v_cache,
+                         const int64_t *slot_mapping, int32_t block_size,
+                         const alora_dims *dims, const alora_extras *extras,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Graph-captured call.  Sec. 3 keeps the activation mask in a tensor of fixed address so that the
  * model's forward pass stays one captured device graph, and App. A's dummy run builds placeholder
  * aLoRA metadata only so that the mask is part of that graph.  Here: alora_qkv_graph_create records

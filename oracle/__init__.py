@@ -119,6 +119,29 @@ def alora_rows(x, W, A, B, aid, active, rows) -> np.ndarray:
     return y
 
 
+def alora_rows_var(x, W, A, B, aid, active, rows, bias=None) -> np.ndarray:
+    """alora_rows with the layer's bias (Algorithm 1: l.apply(x, b)) and one rank per adapter
+    (A[i] is [H, r_i], B[i] is [r_i, N]; Sec. 4.1)."""
+    x, W, rows, aid = _f64(x), _f64(W), _i32(rows), _i32(aid)
+    active = np.ascontiguousarray(active, dtype=np.uint8)
+    H, N = W.shape
+    A = [_f64(a) for a in A]
+    B = [_f64(b) for b in B]
+    ranks = _i32([a.shape[1] for a in A] or [0])
+    for a, b, r in zip(A, B, ranks):
+        assert a.shape == (H, r) and b.shape == (r, N) and r <= 256
+    bias_p = None
+    if bias is not None:
+        bias = _f64(bias)
+        assert bias.shape == (N,)
+        bias_p = _p(bias)
+    y = np.zeros((rows.shape[0], N), dtype=np.float64)
+    _load().oracle_alora_rows_var(ctypes.c_int64(rows.shape[0]), _p(rows), ctypes.c_int32(H), ctypes.c_int32(N),
+                                  _p(ranks), _p(x), _p(W), bias_p, _ptr_table(A), _ptr_table(B),
+                                  _p(aid), _p(active), _p(y))
+    return y
+
+
 def blend_rows(x, W, A, B, aid, paper_mask, rows) -> np.ndarray:
     """Algorithm 1 taken literally (clone, add_adapter, blend with the mask)."""
     x, W, rows, aid = _f64(x), _f64(W), _i32(rows), _i32(aid)
@@ -165,7 +188,7 @@ class ForwardResult:
 
 def alora_qkv_forward(x, token_adapter_ids, token_seg_ids, token_positions, activation_start,
                       W, A, B, slot_mapping, block_size: int, Nq: int, Nkv: int,
-                      k_cache: np.ndarray, v_cache: np.ndarray) -> ForwardResult:
+                      k_cache: np.ndarray, v_cache: np.ndarray, bias=None) -> ForwardResult:
     """The whole path on every row: mask, grouping, projection, q_out and paged K/V store.
 
     k_cache / v_cache are float64 [n_slots, Nkv] holding the cache's previous contents; copies
@@ -176,7 +199,11 @@ def alora_qkv_forward(x, token_adapter_ids, token_seg_ids, token_positions, acti
     mask, act = classify(token_adapter_ids, token_seg_ids, token_positions, activation_start)
     perm, offsets = group(token_adapter_ids, act, len(A))
     rows = np.arange(T, dtype=np.int32)
-    y = alora_rows(x, W, A, B, token_adapter_ids, act, rows)
+    uniform = len({np.asarray(a).shape[1] for a in A}) <= 1
+    if bias is None and uniform:
+        y = alora_rows(x, W, A, B, token_adapter_ids, act, rows)
+    else:
+        y = alora_rows_var(x, W, A, B, token_adapter_ids, act, rows, bias)
     q = np.zeros((T, Nq), dtype=np.float64)
     kc, vc = _f64(k_cache).copy(), _f64(v_cache).copy()
     store_rows(y, rows, Nq, Nkv, slot_mapping, block_size, q, kc, vc)

@@ -116,6 +116,44 @@ void oracle_alora_rows(int64_t n_rows, const int32_t *rows, int32_t H, int32_t N
     }
 }
 
+/* The same projection with the layer's bias and one rank per adapter:
+ *   y = x W + b                   for every row  (Algorithm 1: output = l.apply(x, b); b may be NULL)
+ *   y += (x A_a) B_a              iff active[t], a = aid[t]; A_a is [H, ranks[a]], B_a is [ranks[a], N]
+ *                                 (Sec. 4.1: adapters of different rank are served side by side) */
+void oracle_alora_rows_var(int64_t n_rows, const int32_t *rows, int32_t H, int32_t N, const int32_t *ranks,
+                           const double *x, const double *W, const double *bias,
+                           const double *const *A, const double *const *B,
+                           const int32_t *aid, const uint8_t *active, double *y)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t tok = rows[i];
+        const double *xt = x + (size_t)tok * H;
+        double *yt = y + (size_t)i * N;
+        for (int32_t n = 0; n < N; ++n) yt[n] = 0.0;
+        for (int32_t k = 0; k < H; ++k) {
+            const double xk = xt[k];
+            const double *wk = W + (size_t)k * N;
+            for (int32_t n = 0; n < N; ++n) yt[n] += xk * wk[n];
+        }
+        if (bias)
+            for (int32_t n = 0; n < N; ++n) yt[n] += bias[n];
+        if (active[tok]) {
+            const int32_t ad = aid[tok], ra = ranks[ad];
+            const double *Ar = A[ad], *Br = B[ad];
+            double sv[256];
+            for (int32_t j = 0; j < ra; ++j) sv[j] = 0.0;
+            for (int32_t k = 0; k < H; ++k)
+                for (int32_t j = 0; j < ra; ++j) sv[j] += xt[k] * Ar[(size_t)k * ra + j];
+            for (int32_t n = 0; n < N; ++n) {
+                double dl = 0.0;
+                for (int32_t j = 0; j < ra; ++j) dl += sv[j] * Br[(size_t)j * N + n];
+                yt[n] += dl;
+            }
+        }
+    }
+}
+
 /* Algorithm 1 taken literally, for rows that have an adapter:
  *   base = apply(x); out = add_adapter(clone(base), x); final = base*mask + out*(1-mask)
  * with mask = 1 on pre-activation rows.  Rows of base-model requests (aid = -1) have no

@@ -32,6 +32,10 @@ class AloraWsLayout(ctypes.Structure):
                 ("offsets_off", ctypes.c_size_t), ("total_bytes", ctypes.c_size_t)]
 
 
+class AloraExtras(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("adapter_ranks", ctypes.c_void_p)]
+
+
 class AloraError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -59,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                         ctypes.POINTER(AloraDims), vp, sz, vp]
         L.alora_qkv_validate.argtypes = [vp, vp, vp, i32, ctypes.POINTER(AloraDims)]
+        L.alora_qkv_forward_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                           ctypes.POINTER(AloraDims), ctypes.POINTER(AloraExtras), vp, sz, vp]
         L.alora_qkv_graph_create.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                              ctypes.POINTER(AloraDims), vp, sz, ctypes.POINTER(vp)]
         L.alora_qkv_graph_launch.argtypes = [vp, vp]
@@ -71,7 +77,7 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
                      "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version",
-                     "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy"):
+                     "alora_qkv_forward_ex", "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -164,6 +170,24 @@ def alora_qkv_forward(x, token_adapter_ids, activation_start, W_qkv, A: Sequence
                                 workspace.numel() if workspace is not None else 0, _stream_handle(stream))
     if s:
         raise AloraError(s, "alora_qkv_forward")
+
+
+def alora_qkv_forward_ex(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
+                         q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims,
+                         workspace, bias=None, adapter_ranks=None, stream=None) -> None:
+    """alora_qkv_forward with a layer bias [N] (device tensor) and/or one rank per adapter (host ints)."""
+    ex = AloraExtras(_ptr(bias), None)
+    keep = None
+    if adapter_ranks is not None:
+        keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])
+        ex.adapter_ranks = ctypes.cast(keep, ctypes.c_void_p)
+    s = lib().alora_qkv_forward_ex(_ptr(x), _ptr(token_adapter_ids), _ptr(activation_start), _ptr(W_qkv),
+                                   _ptr_array(A), _ptr_array(B), _ptr(q_out), _ptr(k_cache), _ptr(v_cache),
+                                   _ptr(slot_mapping), block_size, ctypes.byref(dims), ctypes.byref(ex),
+                                   _ptr(workspace), workspace.numel() if workspace is not None else 0,
+                                   _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_qkv_forward_ex")
 
 
 def alora_qkv_graph_create(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,

@@ -164,7 +164,8 @@ int alora_qkv_classify_group(const int32_t *token_adapter_ids, const int32_t *ac
 static int forward_on(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
                       const void *W_qkv, const void *const *A, const void *const *B, void *q_out, void *k_cache,
                       void *v_cache, const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims,
-                      void *workspace, size_t workspace_bytes, void *hip_stream, bool allow_timing)
+                      void *workspace, size_t workspace_bytes, void *hip_stream, bool allow_timing,
+                      const alora_extras *extras = nullptr)
 {
     int s = check_dims(dims);
     if (s) return s;
@@ -189,6 +190,21 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
             tb.p[i] = B[i];
         }
     }
+    RankTable ranks;
+    for (int i = 0; i < ALORA_MAX_ADAPTERS; ++i) ranks.r[i] = (uint8_t)dims->rank;
+    const void *bias = nullptr;
+    if (extras) {
+        bias = extras->bias;
+        if (bias && misaligned16(bias)) return ALORA_EINVAL;
+        if (extras->adapter_ranks) {
+            for (int i = 0; i < dims->n_adapters; ++i) {
+                const int ri = extras->adapter_ranks[i];
+                if (ri < 1 || ri > dims->rank) return ALORA_ESHAPE;
+                if (dims->dtype == ALORA_BF16 && ri % 8) return ALORA_ESHAPE;
+                ranks.r[i] = (uint8_t)ri;
+            }
+        }
+    }
     Layout l;
     s = check_ws(dims, workspace, workspace_bytes, &l);
     if (s) return s;
@@ -196,6 +212,8 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
 
     Fwd f = {};
     fill_common(f, dims, l, workspace, hip_stream);
+    f.bias = bias;
+    f.ranks = ranks;
     f.block_size = block_size;
     f.x = x; f.W = W_qkv; f.aid = token_adapter_ids; f.start = activation_start; f.slot = slot_mapping;
     f.q = q_out; f.kc = k_cache; f.vc = v_cache;
@@ -228,6 +246,15 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
 {
     return forward_on(x, token_adapter_ids, activation_start, W_qkv, A, B, q_out, k_cache, v_cache, slot_mapping,
                       block_size, dims, workspace, workspace_bytes, hip_stream, true);
+}
+
+int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                         const void *W_qkv, const void *const *A, const void *const *B, void *q_out, void *k_cache,
+                         void *v_cache, const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims,
+                         const alora_extras *extras, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return forward_on(x, token_adapter_ids, activation_start, W_qkv, A, B, q_out, k_cache, v_cache, slot_mapping,
+                      block_size, dims, workspace, workspace_bytes, hip_stream, true, extras);
 }
 
 struct alora_graph {

@@ -10,7 +10,7 @@ namespace alora {
 
 // One workgroup per adapted row; wavefront kq sums a quarter of the hidden dimension for rank
 // column j = lane, the four partial sums are added in fixed order.
-__global__ __launch_bounds__(256) void shrink_f32_kernel(const float *__restrict__ x, PtrTable A,
+__global__ __launch_bounds__(256) void shrink_f32_kernel(const float *__restrict__ x, PtrTable A, RankTable ranks,
                                                          const int32_t *__restrict__ aid,
                                                          const int32_t *__restrict__ perm,
                                                          const int32_t *__restrict__ offsets, int L, int H, int r,
@@ -23,12 +23,13 @@ __global__ __launch_bounds__(256) void shrink_f32_kernel(const float *__restrict
     const int a = aid[t];
     const float *xr = x + (size_t)t * H;
     const float *Aa = (const float *)A.p[a];
+    const int ra = ranks.r[a];   // this adapter's rank: A_a is [H, ra]; S keeps the common row pitch r
     const int j = threadIdx.x & 63, kq = threadIdx.x >> 6;
     const int kchunk = (H + 3) / 4;
     const int k0 = kq * kchunk, k1 = min(H, k0 + kchunk);
     float acc = 0.f;
-    if (j < r)
-        for (int k = k0; k < k1; ++k) acc = fmaf(xr[k], Aa[(size_t)k * r + j], acc);
+    if (j < ra)
+        for (int k = k0; k < k1; ++k) acc = fmaf(xr[k], Aa[(size_t)k * ra + j], acc);
     red[kq][j] = acc;
     __syncthreads();
     if (kq == 0 && j < r) S[(size_t)t * r + j] = ((red[0][j] + red[1][j]) + red[2][j]) + red[3][j];
@@ -37,7 +38,8 @@ __global__ __launch_bounds__(256) void shrink_f32_kernel(const float *__restrict
 constexpr int FBM = 64, FBN = 64, FBK = 16;
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
-    const float *__restrict__ x, const float *__restrict__ W, PtrTable B, const float *__restrict__ S,
+    const float *__restrict__ x, const float *__restrict__ W, const float *__restrict__ bias, PtrTable B,
+    RankTable ranks, const float *__restrict__ S,
     const int32_t *__restrict__ aid, const int32_t *__restrict__ seg, const int32_t *__restrict__ pos,
     const int32_t *__restrict__ start, const int64_t *__restrict__ slot, float *__restrict__ q,
     float *__restrict__ kc, float *__restrict__ vc, int T, int H, int Nq, int Nkv, int r)
@@ -79,11 +81,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         if (t >= T) continue;
         const int a = effective_adapter(aid, seg, pos, start, t);
         float4 y = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+        if (bias) {   // part of the base output of every row
+            const float4 b4 = *(const float4 *)(bias + n);
+            y.x += b4.x; y.y += b4.y; y.z += b4.z; y.w += b4.w;
+        }
         if (a >= 0) {
             const float *Ba = (const float *)B.p[a];
             const float *Sr = S + (size_t)t * r;
             float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int j = 0; j < r; ++j) {
+            const int ra = ranks.r[a];
+            for (int j = 0; j < ra; ++j) {
                 const float s = Sr[j];
                 const float4 b4 = *(const float4 *)(Ba + (size_t)j * N + n);
                 d.x = fmaf(s, b4.x, d.x); d.y = fmaf(s, b4.y, d.y);
@@ -105,7 +112,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 int launch_shrink_f32(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;
-    hipLaunchKernelGGL(shrink_f32_kernel, dim3(f.T), dim3(256), 0, f.stream, (const float *)f.x, A, f.aid,
+    hipLaunchKernelGGL(shrink_f32_kernel, dim3(f.T), dim3(256), 0, f.stream, (const float *)f.x, A, f.ranks, f.aid,
                        f.perm, f.offsets, f.L, f.H, f.r, (float *)f.S);
     return (int)hipGetLastError();
 }
@@ -114,8 +121,8 @@ int launch_gemm_f32(const Fwd &f, const PtrTable &B)
 {
     if (f.T == 0) return 0;
     dim3 grid((f.N + FBN - 1) / FBN, (f.T + FBM - 1) / FBM);
-    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, f.stream, (const float *)f.x, (const float *)f.W, B,
-                       (const float *)f.S, f.aid, f.seg, f.pos, f.start, f.slot, (float *)f.q, (float *)f.kc,
+    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, f.stream, (const float *)f.x, (const float *)f.W,
+                       (const float *)f.bias, B, f.ranks, (const float *)f.S, f.aid, f.seg, f.pos, f.start, f.slot, (float *)f.q, (float *)f.kc,
                        (float *)f.vc, f.T, f.H, f.Nq, f.Nkv, f.r);
     return (int)hipGetLastError();
 }

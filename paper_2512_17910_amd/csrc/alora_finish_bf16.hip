@@ -26,6 +26,7 @@ constexpr int FIN_COLS = 256;  // features per workgroup: 32 threads x 8 feature
 template <int SPLITS>
 __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restrict__ partial,
                                                            const void *__restrict__ S_any, int s_splits, PtrTable B,
+                                                           RankTable ranks, const bf16_t *__restrict__ bias,
                                                            const int32_t *__restrict__ perm,
                                                            const int4 *__restrict__ blocktab,
                                                            const int64_t *__restrict__ slot, bf16_t *__restrict__ q,
@@ -43,6 +44,7 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
     const int n0 = blockIdx.y * FIN_COLS;
     const int tid = threadIdx.x;
     const bool adapted = a < L;
+    const int ra = adapted ? ranks.r[a] : 0;   // this group's rank; S and B_a rows beyond it do not exist
     const int i = tid >> 5, c = tid & 31, n = n0 + 8 * c;
     const bool live = i < cnt && n < N;
     const int t = i < cnt ? perm[j0 + i] : -1;
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
     if (adapted) {
         // S of row i, rank columns c, c+32
         if (t >= 0) {
-            for (int j = c; j < r; j += 32) {
+            for (int j = c; j < ra; j += 32) {
                 float sj = 0.f;
                 if (s_splits > 1) {
                     for (int ks = 0; ks < s_splits; ++ks) sj += S_part[((size_t)ks * T + t) * r + j];
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
         }
         // B[a][:, n0 : n0+256]: rank rows x 32 chunks of 8 features
         const bf16_t *Ba = (const bf16_t *)B.p[a];
-        for (int idx = tid; idx < r * (FIN_COLS / 8); idx += 1024) {
+        for (int idx = tid; idx < ra * (FIN_COLS / 8); idx += 1024) {
             const int j = idx / (FIN_COLS / 8), cc = idx % (FIN_COLS / 8);
             u32x4 v = {0u, 0u, 0u, 0u};
             if (n0 + 8 * cc < N) v = *(const u32x4 *)(Ba + (size_t)j * N + n0 + 8 * cc);
@@ -91,9 +93,16 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
         y[0] += plo[s].x; y[1] += plo[s].y; y[2] += plo[s].z; y[3] += plo[s].w;
         y[4] += phi[s].x; y[5] += phi[s].y; y[6] += phi[s].z; y[7] += phi[s].w;
     }
+    if (bias) {   // part of the base output of every row
+        const u32x4 bv = *(const u32x4 *)(bias + n);
+        y[0] += __uint_as_float(bv.x << 16); y[1] += __uint_as_float(bv.x & 0xffff0000u);
+        y[2] += __uint_as_float(bv.y << 16); y[3] += __uint_as_float(bv.y & 0xffff0000u);
+        y[4] += __uint_as_float(bv.z << 16); y[5] += __uint_as_float(bv.z & 0xffff0000u);
+        y[6] += __uint_as_float(bv.w << 16); y[7] += __uint_as_float(bv.w & 0xffff0000u);
+    }
     if (adapted) {
         float d[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int j = 0; j < r; ++j) {
+        for (int j = 0; j < ra; ++j) {
             const float sj = s_lds[i][j];
             const u32x4 bv = *(const u32x4 *)&b_lds[j][8 * c];
             d[0] = fmaf(sj, __uint_as_float(bv.x << 16), d[0]);
@@ -129,7 +138,7 @@ static void launch_finish(const Fwd &f, const PtrTable &B)
 {
     const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
     hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
-                       f.S, plan_shrink(f.T, f.H, f.N, f.L).splits, B, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
+                       f.S, plan_shrink(f.T, f.H, f.N, f.L).splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
                        (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
 }
 

@@ -56,6 +56,8 @@ struct GemmArgs {
     int mtiles, ntiles;
     int kps;          // split mode: 32-wide K-slices per split
     float *partial;   // split mode: [splits][T][N] fp32
+    const bf16_t *bias;   // [N] or null: added to every row before rounding (fused mode)
+    RankTable ranks;      // per adapter: B_a has ranks.r[a] rows
 };
 
 // Buffer descriptor of a raw byte buffer (stride 0, 32-bit data format): offsets at or past
@@ -288,8 +290,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         for (int e = 0; e < n_exp; ++e) {
             const int j = e / epa, k0 = (e - j * epa) * BK;
             const int a = __builtin_amdgcn_readfirstlane(plist[j]);
+            const int ra = __builtin_amdgcn_readfirstlane((int)g.ranks.r[a]);   // rows of B_a; S columns past it are zero, B rows past it do not exist
             const rsrc_t rb =
-                make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(g.r * g.N - n0) * 2);
+                make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(ra * g.N - n0) * 2);
             uint32_t vx[4], vw[NCW];
 #pragma unroll
             for (int ii = 0; ii < 4; ++ii) {
@@ -301,7 +304,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             for (int jj = 0; jj < NCW; ++jj) {
                 const int kk = k0 + w_k(jj, lane);
                 const int srow = kk >= g.r ? kk - g.r : kk;   // [B ; B]: the hi and the lo half meet the same rows
-                const bool ok = (kk < g.kx) & w_col_ok(jj, lane);
+                const bool ok = (kk < g.kx) & (srow < ra) & w_col_ok(jj, lane);
                 vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
             }
 #pragma unroll
@@ -431,6 +434,17 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 8;
+        // bias of the four consecutive features this lane holds per (feature tile, register quad):
+        // part of the base output of every row, added in fp32 before the one rounding
+        u32x2 bias4[NTW][4];   // kept packed (two bf16 per register) until it is added
+#pragma unroll
+        for (int a = 0; a < NTW; ++a)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int nf = n0 + wn * 32 * NTW + a * 32 + 8 * gq + 4 * lh;
+                bias4[a][gq] = (u32x2){0u, 0u};
+                if (g.bias && nf < g.N) bias4[a][gq] = *(const u32x2 *)(g.bias + nf);
+            }
         // destination of this lane's 8 features: 0 = q_out, 1 = K cache, 2 = V cache, -1 = none
         int region = -1, col = 0;
         if (er < RPI && n < g.N) {
@@ -444,8 +458,10 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             for (int a = 0; a < NTW; ++a) {
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
-                    const f32x2 p0 = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1]};
-                    const f32x2 p1 = {acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
+                    f32x2 p0 = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1]};
+                    f32x2 p1 = {acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
+                    p0 += (f32x2){__uint_as_float(bias4[a][gq].x << 16), __uint_as_float(bias4[a][gq].x & 0xffff0000u)};
+                    p1 += (f32x2){__uint_as_float(bias4[a][gq].y << 16), __uint_as_float(bias4[a][gq].y & 0xffff0000u)};
                     u32x2 v;
                     v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2));
                     v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2));
@@ -543,6 +559,8 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projectio
     g.ntiles = (f.N + 64 * plan.ntw - 1) / (64 * plan.ntw);
     g.kps = plan.kps * (KBLK / BK);
     g.partial = f.partial;
+    g.bias = (const bf16_t *)f.bias;
+    g.ranks = f.ranks;
     if (plan.ntw == 4) launch_ntw<4>(g, B, plan.splits, f.stream);
     else if (plan.ntw == 3) launch_ntw<3>(g, B, plan.splits, f.stream);
     else launch_ntw<2>(g, B, plan.splits, f.stream);

@@ -19,12 +19,19 @@ struct PtrTable {
     const void *p[ALORA_MAX_ADAPTERS];
 };
 
+// Rank of every adapter (A_i is [hidden, r_i], B_i is [r_i, N]), passed to kernels by value.
+struct RankTable {
+    uint8_t r[ALORA_MAX_ADAPTERS];
+};
+
 // Everything one forward call needs, resolved on the host.
 struct Fwd {
     int dtype, T, H, Nq, Nkv, N, L, r, G;
     long long n_slots;
     int block_size;
     const void *x, *W;
+    const void *bias;    // [N] or null: added to the base output of every row (Algorithm 1, l.apply(x, b))
+    RankTable ranks;     // per adapter, <= r
     const int32_t *aid, *seg, *pos, *start;
     const int64_t *slot;
     void *q, *kc, *vc;

@@ -35,7 +35,7 @@ constexpr int SHRINK_ROWS = 32;
 
 // KSL: hidden-dimension chunk per LDS buffer; NT: 32-wide rank tiles (1 for rank <= 32, else 2)
 template <int KSL, int NT>
-__global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restrict__ x, PtrTable A,
+__global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restrict__ x, PtrTable A, RankTable ranks,
                                                           const int32_t *__restrict__ perm,
                                                           const int4 *__restrict__ blocktab, int L, int H, int r, uint32_t x_bytes,
                                                           int T, int kper, void *__restrict__ S_out)
@@ -64,13 +64,14 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bf16_t *Aa = (const bf16_t *)A.p[a];
+    const int rk = ranks.r[a];   // this adapter's rank (multiple of 8): A_a is [H, rk]; S keeps the common pitch r
 
     if (tid < SHRINK_ROWS) rows_t[tid] = tid < cnt ? perm[j0 + tid] : -1;
     __syncthreads();
 
     const int li = lane & 31, lh = lane >> 5;
     const int s16 = lane & 15, blk = (lane >> 4) & 1;
-    const int row_bytes = 2 * r;
+    const int row_bytes = 2 * rk;
     f32x16 acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
     // all copies of the chunk starting at hidden index ks0
     // Buffer descriptors: reads past the end of A (a short last chunk) return zeros by themselves;
     // masked token lanes get an offset past the end of x.
-    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void *)Aa, 0, H * r * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void *)Aa, 0, H * rk * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)x, 0, (int)x_bytes, 0x00020000);
     // per-lane byte offsets of the token copies at hidden index 0 (0xffffffff = masked)
     uint32_t xoff[XI];
@@ -100,9 +101,9 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
             const uint32_t off = (uint32_t)q * 1024u + 16u * lane;
             // rows ks0 .. ks0+klen of [H, r] are contiguous; what lies beyond them in the buffer is
             // either past the end of A (zeros) or masked here
-            const uint32_t vo = off < (uint32_t)klen * r * 2 ? off : 0xffffffffu;
+            const uint32_t vo = off < (uint32_t)klen * rk * 2 ? off : 0xffffffffu;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void *)((lds_byte *)as + q * 1024),
-                                                     16, vo, (uint32_t)ks0 * r * 2, 0, 0);
+                                                     16, vo, (uint32_t)ks0 * rk * 2, 0, 0);
         }
         // tokens: instruction q copies RPI rows; lane -> physical chunk, holding logical chunk
         // (physical ^ (row % 16))
@@ -198,7 +199,8 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
         const int tt = rows_t[row];
         if (tt < 0 || col >= r) continue;
         const int nt = col >> 5, c = col & 31;
-        const float s = ((red[0][nt][row][c] + red[1][nt][row][c]) + red[2][nt][row][c]) + red[3][nt][row][c];
+        // rank columns past this adapter's own rank are zero (the consumers walk the common rank r)
+        const float s = col < rk ? ((red[0][nt][row][c] + red[1][nt][row][c]) + red[2][nt][row][c]) + red[3][nt][row][c] : 0.f;
         if (ranges) {
             ((float *)S_out)[((size_t)blockIdx.y * T + tt) * r + col] = s;
         } else {
@@ -231,10 +233,10 @@ int launch_shrink_bf16(const Fwd &f, const PtrTable &A)
     const ShrinkPlan sp = plan_shrink(f.T, f.H, f.N, f.L);
     const dim3 grid(f.n_blocks, sp.splits);
     if (f.r <= 32)
-        hipLaunchKernelGGL((shrink_bf16_kernel<512, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
+        hipLaunchKernelGGL((shrink_bf16_kernel<512, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.ranks, f.perm,
                            f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), f.T, sp.kper, f.S);
     else
-        hipLaunchKernelGGL((shrink_bf16_kernel<256, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.perm,
+        hipLaunchKernelGGL((shrink_bf16_kernel<256, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.ranks, f.perm,
                            f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), f.T, sp.kper, f.S);
     return (int)hipGetLastError();
 }

@@ -22,7 +22,7 @@ import numpy as np
 SEED = 0x2512_1791_0A10_4A5D  # one fixed 64-bit constant; streams select the array
 
 # stream ids (second half of the Philox key)
-_ST_X, _ST_W, _ST_A, _ST_B, _ST_STRUCT, _ST_SLOTS, _ST_CACHE = 1, 2, 3, 4, 5, 6, 7
+_ST_X, _ST_W, _ST_A, _ST_B, _ST_STRUCT, _ST_SLOTS, _ST_CACHE, _ST_BIAS = 1, 2, 3, 4, 5, 6, 7, 8
 
 
 # --------------------------------------------------------------------------------------
@@ -97,6 +97,8 @@ class Workload:
     activation_start: np.ndarray = None    # int32 [G]
     slot_mapping: np.ndarray = None        # int64 [T]
     cached_prefix_slots: Optional[np.ndarray] = None  # slots of skipped, already cached prefixes
+    bias: Optional[np.ndarray] = None      # [N] layer bias (Algorithm 1's b), storage dtype; None = no bias
+    adapter_ranks: Optional[List[int]] = None   # per-adapter rank r_i <= rank: A[i] is [hidden, r_i], B[i] is [r_i, N]
 
     @property
     def T(self) -> int:
@@ -181,6 +183,22 @@ def assemble(name: str, dtype: str, hidden: int, n_q_heads: int, n_kv_heads: int
         w.A = [_normal(wk, _ST_A, i, (hidden, rank), hidden ** -0.5, dtype) for i in range(n_adapters)]
         w.B = [_normal(wk, _ST_B, i, (rank, N), rank ** -0.5, dtype) for i in range(n_adapters)]
     return w
+
+
+def with_variants(w: Workload, ranks: Optional[Sequence[int]] = None, bias: bool = False, seed: int = SEED) -> Workload:
+    """The same batch with adapter-layout variants: adapter i keeps only its first ranks[i] rank
+    components (A[i][:, :r_i], B[i][:r_i, :]), and/or a seeded layer bias ~ N(0, 1)."""
+    import copy
+    v = copy.copy(w)
+    v.name = w.name + "+variants"
+    if ranks is not None:
+        assert len(ranks) == w.n_adapters and all(1 <= r <= w.rank for r in ranks)
+        v.adapter_ranks = [int(r) for r in ranks]
+        v.A = [np.ascontiguousarray(a[:, :r]) for a, r in zip(w.A, ranks)]
+        v.B = [np.ascontiguousarray(b[:r, :]) for b, r in zip(w.B, ranks)]
+    if bias:
+        v.bias = _normal(seed, _ST_BIAS, 0, (w.N,), 1.0, w.dtype)
+    return v
 
 
 def sample_rows(w: Workload, n: int) -> np.ndarray:
@@ -272,7 +290,32 @@ def config5(seed: int = SEED, with_values: bool = True) -> Workload:
     return w
 
 
-CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+def config6(seed: int = SEED, with_values: bool = True) -> Workload:
+    """Adapter-layout variants in one prefill batch (not one of the five headline configurations):
+    Llama-3-8B shapes, 8 sequences x 512 tokens mixing base-model requests, standard LoRAs of rank 8
+    (activation at 0) and aLoRAs of rank 32 activated in the second half, plus a layer bias."""
+    g = _rng(seed ^ 6, _ST_STRUCT)
+    kinds = ["alora", "lora", "base", "alora", "lora", "alora", "base", "alora"]
+    ranks = [32, 32, 32, 32, 8, 8, 8, 8]          # adapters 0-3: aLoRAs, 4-7: standard LoRAs
+    segs = []
+    for s, kind in enumerate(kinds):
+        if kind == "base":
+            segs.append(Segment(s, 0, 512, -1, 0))
+        elif kind == "lora":
+            segs.append(Segment(s, 0, 512, 4 + int(g.integers(0, 4)), 0))
+        else:
+            segs.append(Segment(s, 0, 512, int(g.integers(0, 4)), int(g.integers(256, 512))))
+    w = assemble("cfg6-8b-mixed-variants", "bf16", 4096, 32, 8, 128, 8, 32, 16, segs, [512] * 8,
+                 seed=seed ^ 6, weight_key=_W8B, with_values=with_values)
+    if not with_values:
+        w.adapter_ranks = ranks
+        return w
+    v = with_variants(w, ranks=ranks, bias=True, seed=seed ^ 6)
+    v.name = w.name
+    return v
+
+
+CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6}
 
 
 def small_mixed(dtype: str = "bf16", hidden: int = 256, n_q_heads: int = 4, n_kv_heads: int = 2,

@@ -62,6 +62,7 @@ class DeviceBatch:
                                  w.n_kv_heads, w.head_dim, w.n_adapters, w.rank, w.n_segments, w.n_slots,
                                  self.seg, self.pos)
         self.ws = ab.alloc_workspace(self.dims)
+        self.bias = to_dev(w.bias, dt) if w.bias is not None else None
 
     def reset(self):
         self.q.zero_()
@@ -69,6 +70,13 @@ class DeviceBatch:
         self.vc.copy_(self.v0)
 
     def forward(self, aid=None, A=None, B=None):
+        if self.bias is not None or self.w.adapter_ranks is not None:
+            ab.alora_qkv_forward_ex(self.x, self.aid if aid is None else aid, self.start, self.W,
+                                    self.A if A is None else A, self.B if B is None else B,
+                                    self.q, self.kc, self.vc, self.slot, self.w.block_size, self.dims, self.ws,
+                                    bias=self.bias, adapter_ranks=self.w.adapter_ranks)
+            torch.cuda.synchronize()
+            return
         ab.alora_qkv_forward(self.x, self.aid if aid is None else aid, self.start, self.W,
                              self.A if A is None else A, self.B if B is None else B,
                              self.q, self.kc, self.vc, self.slot, self.w.block_size, self.dims, self.ws)

@@ -17,8 +17,10 @@ def _oracle_full(w):
     x, W, A, B = host_operands(w)
     k0 = wl.widen_f64(wl.cache_fill(w.n_slots, w.Nkv, w.dtype, 0), w.dtype)
     v0 = wl.widen_f64(wl.cache_fill(w.n_slots, w.Nkv, w.dtype, 1), w.dtype)
+    bias = wl.widen_f64(w.bias, w.dtype) if w.bias is not None else None
     return oracle.alora_qkv_forward(x, w.token_adapter_ids, w.token_seg_ids, w.token_positions,
-                                    w.activation_start, W, A, B, w.slot_mapping, w.block_size, w.Nq, w.Nkv, k0, v0)
+                                    w.activation_start, W, A, B, w.slot_mapping, w.block_size, w.Nq, w.Nkv, k0, v0,
+                                    bias=bias)
 
 
 def _check_full(w, db=None, elementwise=True):
@@ -251,3 +253,53 @@ def test_random_shapes_match_the_oracle(dtype, n_cases):
         kw = _random_shape(rng, dtype)
         print(f"[shape] {kw}", flush=True)
         _check_full(wl.small_mixed(**kw))
+
+
+# ---- adapter-layout variants: layer bias (Algorithm 1) and one rank per adapter (Sec. 4.1) ----------
+VARIANTS = [
+    dict(base=dict(dtype="bf16", seed=21, rank=32, n_adapters=4, seq_lens=(300, 41, 77, 256)), ranks=(8, 32, 16, 24), bias=True),
+    dict(base=dict(dtype="bf16", seed=22, rank=64, n_adapters=3, hidden=192, seq_lens=(130, 9, 64)), ranks=(64, 8, 40), bias=False),
+    dict(base=dict(dtype="bf16", seed=23, rank=16, n_adapters=2), ranks=None, bias=True),
+    dict(base=dict(dtype="f32", seed=24, rank=12, n_adapters=3, hidden=100, n_q_heads=3, n_kv_heads=1, head_dim=20,
+                   seq_lens=(70, 9, 130)), ranks=(1, 12, 5), bias=True),
+]
+
+
+@pytest.mark.parametrize("v", VARIANTS, ids=[f"{v['base']['dtype']}-{v['base']['seed']}" for v in VARIANTS])
+def test_bias_and_per_adapter_ranks_match_the_oracle(v):
+    _check_full(wl.with_variants(wl.small_mixed(**v["base"]), ranks=v["ranks"], bias=v["bias"]))
+
+
+@pytest.mark.parametrize("ft,sp", [(4, 1), (3, 1), (2, 1), (2, 4), (3, 2)], ids=lambda t: str(t))
+def test_variants_under_every_tiling(tuning, ft, sp):
+    tuning(ft, sp)
+    v = VARIANTS[0]
+    _check_full(wl.with_variants(wl.small_mixed(**v["base"]), ranks=v["ranks"], bias=v["bias"]))
+
+
+def test_zero_padded_adapters_equal_native_ranks_on_base_rows_and_within_tolerance_elsewhere():
+    """The caller-side alternative (pad every adapter with zero rank components up to the common rank)
+    and the native per-adapter ranks describe the same function."""
+    base = wl.small_mixed("bf16", seed=25, rank=32, n_adapters=3, seq_lens=(200, 90))
+    ranks = (8, 32, 16)
+    native = wl.with_variants(base, ranks=ranks)
+    import copy
+    padded = copy.copy(base)
+    padded.A = [np.where(np.arange(32)[None, :] < r, a, 0).astype(a.dtype) for a, r in zip(base.A, ranks)]
+    padded.B = [np.where(np.arange(32)[:, None] < r, b, 0).astype(b.dtype) for b, r in zip(base.B, ranks)]
+    d1, d2 = DeviceBatch(native), DeviceBatch(padded)
+    d1.forward()
+    d2.forward()
+    assert np.array_equal(raw_bits(d1.q), raw_bits(d2.q))
+    assert np.array_equal(raw_bits(d1.kc), raw_bits(d2.kc)) and np.array_equal(raw_bits(d1.vc), raw_bits(d2.vc))
+
+
+def test_forward_ex_rejects_bad_ranks():
+    w = wl.small_mixed("bf16", seed=1)
+    db = DeviceBatch(w)
+    for bad in ([w.rank + 8] * w.n_adapters, [0] * w.n_adapters, [4] * w.n_adapters):
+        with pytest.raises(ab.AloraError) as e:
+            ab.alora_qkv_forward_ex(db.x, db.aid, db.start, db.W, db.A, db.B, db.q, db.kc, db.vc, db.slot,
+                                    w.block_size, db.dims, db.ws, adapter_ranks=bad)
+        assert e.value.status == ab.ALORA_ESHAPE
+    assert np.array_equal(raw_bits(db.kc), raw_bits(db.k0))

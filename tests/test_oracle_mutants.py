@@ -45,6 +45,11 @@ MUTANTS = {
                          "for (int64_t t = T - 1; t >= 0; --t)\n            if (active[t] && aid[t] == a) perm[n++] = (int32_t)t;"),
     "group_ignores_mask": ("if (active[t]) offsets[aid[t] + 1] += 1;", "if (aid[t] >= 0) offsets[aid[t] + 1] += 1;"),
     "blend_mask_swapped": ("yr[n] = base * m + out * (1.0 - m);", "yr[n] = out * m + base * (1.0 - m);"),
+    "var_bias_dropped": ("yt[n] += bias[n];", "yt[n] += 0.0 * bias[n];"),
+    "var_bias_only_on_adapted_rows": ("        if (bias)\n            for", "        if (bias && active[tok])\n            for"),
+    "var_rank_of_wrong_adapter": ("const int32_t ad = aid[tok], ra = ranks[ad];", "const int32_t ad = aid[tok], ra = ranks[0];"),
+    "var_A_pitch_is_common_rank": ("sv[j] += xt[k] * Ar[(size_t)k * ra + j];", "sv[j] += xt[k] * Ar[(size_t)k * ranks[0] + j];"),
+    "var_delta_sign": ("yt[n] += dl;", "yt[n] -= dl;"),
     "coords_divisor": ("block[t] = slot[t] / block_size;", "block[t] = slot[t] / (block_size + 1);"),
 }
 

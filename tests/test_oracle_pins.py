@@ -328,7 +328,53 @@ def pin_column_split():
     assert (res.v_cache[wr] != res3.v_cache[wr]).any(axis=1).all()
 
 
-PINS = [pin_worked_example, pin_one_hot_closed_form, pin_activation_zero_is_lora,
+def pin_variants_small_integers_exact():
+    """Bias (Algorithm 1: base output = l.apply(x, b)) and one rank per adapter (Sec. 4.1): with
+    small-integer data every product and sum is exact in fp64, so the result must EQUAL the
+    definition written with numpy, whatever the summation order."""
+    rng = np.random.default_rng(77)
+    T, H, N = 9, 5, 7
+    ranks = [1, 3, 2]
+    x, W = _rand_ints(rng, (T, H)), _rand_ints(rng, (H, N))
+    A = [_rand_ints(rng, (H, r)) for r in ranks]
+    B = [_rand_ints(rng, (r, N)) for r in ranks]
+    b = _rand_ints(rng, (N,))
+    aid = np.array([0, 1, 2, -1, 2, 1, 0, -1, 1], np.int32)
+    act = np.array([1, 0, 1, 0, 1, 1, 0, 0, 1], np.uint8)
+    rows = np.arange(T, dtype=np.int32)
+    for bias in (None, b):
+        y = oracle.alora_rows_var(x, W, A, B, aid, act, rows, bias)
+        for t in range(T):
+            want = x[t] @ W + (bias if bias is not None else 0)
+            if act[t]:
+                want = want + (x[t] @ A[aid[t]]) @ B[aid[t]]
+            assert np.array_equal(y[t], want), (t, bias is not None)
+
+
+def pin_variants_reduce_to_the_plain_form():
+    """Equal ranks and no bias: the variant routine IS the plain one; zero-padding an adapter's missing
+    rank components changes nothing (adding exact zeros); W = 0 with no adapter leaves the bias."""
+    rng = np.random.default_rng(78)
+    T, H, N, r = 11, 16, 12, 4
+    x, W = rng.standard_normal((T, H)), rng.standard_normal((H, N))
+    A = [rng.standard_normal((H, r)) for _ in range(3)]
+    B = [rng.standard_normal((r, N)) for _ in range(3)]
+    aid = rng.integers(-1, 3, T).astype(np.int32)
+    act = ((aid >= 0) & (rng.random(T) < 0.6)).astype(np.uint8)
+    rows = np.arange(T, dtype=np.int32)
+    assert np.array_equal(oracle.alora_rows_var(x, W, A, B, aid, act, rows), oracle.alora_rows(x, W, A, B, aid, act, rows))
+    ranks = [1, 4, 2]
+    At = [a[:, :k].copy() for a, k in zip(A, ranks)]
+    Bt = [b[:k, :].copy() for b, k in zip(B, ranks)]
+    Ap = [np.where(np.arange(r)[None, :] < k, a, 0.0) for a, k in zip(A, ranks)]
+    Bp = [np.where(np.arange(r)[:, None] < k, b, 0.0) for b, k in zip(B, ranks)]
+    assert np.array_equal(oracle.alora_rows_var(x, W, At, Bt, aid, act, rows), oracle.alora_rows(x, W, Ap, Bp, aid, act, rows))
+    bias = rng.standard_normal(N)
+    y = oracle.alora_rows_var(x, np.zeros_like(W), At, Bt, aid, np.zeros(T, np.uint8), rows, bias)
+    assert np.array_equal(y, np.tile(bias, (T, 1)))
+
+
+PINS = [pin_variants_small_integers_exact, pin_variants_reduce_to_the_plain_form, pin_worked_example, pin_one_hot_closed_form, pin_activation_zero_is_lora,
         pin_pre_activation_rows_are_base_exactly, pin_zero_B_and_never_activated,
         pin_blend_equals_select, pin_mask_closed_form_counts, pin_group_matches_stable_sort,
         pin_brute_force_exact, pin_linearity, pin_row_permutation, pin_paged_store,
