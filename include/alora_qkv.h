@@ -166,7 +166,8 @@ int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const 
  * ONE alora_qkv_forward with exactly these pointers and sizes into a HIP graph (on a stream of its
  * own; nothing runs) and hands back the instantiated graph; every alora_qkv_graph_launch replays
  * the whole call (classification/grouping, shrink, projection, stores) on `hip_stream`.
- *   - Arguments, layouts and preconditions are those of alora_qkv_forward; T must be > 0.
+ *   - Arguments, layouts and preconditions are those of alora_qkv_forward_ex (extras may be NULL;
+ *     the rank array is read at creation, the bias pointer is baked in); T must be > 0.
  *   - All addresses are baked in: before a launch the caller rewrites the CONTENTS of x,
  *     token_adapter_ids, dims->token_seg_ids, dims->token_positions, activation_start and
  *     slot_mapping in place.  A batch with fewer than T rows is padded with rows that have
@@ -182,8 +183,8 @@ int alora_qkv_graph_create(const void *x, const int32_t *token_adapter_ids, cons
                            const void *W_qkv, const void *const *A, const void *const *B,
                            void *q_out, void *k_cache, void *v_cache,
                            const int64_t *slot_mapping, int32_t block_size,
-                           const alora_dims *dims, void *workspace, size_t workspace_bytes,
-                           alora_graph **out);
+                           const alora_dims *dims, const alora_extras *extras,
+                           void *workspace, size_t workspace_bytes, alora_graph **out);
 int alora_qkv_graph_launch(alora_graph *graph, void *hip_stream);
 int alora_qkv_graph_destroy(alora_graph *graph);
 

@@ -20,7 +20,7 @@ are interchangeable exactly when the paper says they are.  (The hash function of
 product is "parity unpinned": any collision-resistant hash is valid; what is pinned is which
 blocks share an identity.)
 
-Readings where the paper is silent (listed in the design doc):
+Readings where the paper is silent:
   - a block "holds tokens processed with the adapter" iff it contains a position >= activation_start,
     i.e. (b+1)*block_size > activation_start; a standard LoRA is activation_start = 0, a base request
     has adapter -1 (no block ever carries an id);

@@ -66,7 +66,8 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_forward_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                            ctypes.POINTER(AloraDims), ctypes.POINTER(AloraExtras), vp, sz, vp]
         L.alora_qkv_graph_create.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
-                                             ctypes.POINTER(AloraDims), vp, sz, ctypes.POINTER(vp)]
+                                             ctypes.POINTER(AloraDims), ctypes.POINTER(AloraExtras), vp, sz,
+                                             ctypes.POINTER(vp)]
         L.alora_qkv_graph_launch.argtypes = [vp, vp]
         L.alora_qkv_graph_destroy.argtypes = [vp]
         L.alora_status_string.argtypes = [ctypes.c_int]
@@ -191,14 +192,21 @@ def alora_qkv_forward_ex(x, token_adapter_ids, activation_start, W_qkv, A: Seque
 
 
 def alora_qkv_graph_create(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
-                           q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims, workspace):
+                           q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims, workspace,
+                           bias=None, adapter_ranks=None):
     """Record one forward call with these buffers into a HIP graph; returns an opaque handle for
     alora_qkv_graph_launch / alora_qkv_graph_destroy.  The caller keeps every tensor alive and rewrites
     their contents in place between launches."""
     h = ctypes.c_void_p(None)
+    ex = AloraExtras(_ptr(bias), None)
+    keep = None
+    if adapter_ranks is not None:
+        keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])
+        ex.adapter_ranks = ctypes.cast(keep, ctypes.c_void_p)
     s = lib().alora_qkv_graph_create(_ptr(x), _ptr(token_adapter_ids), _ptr(activation_start), _ptr(W_qkv),
                                      _ptr_array(A), _ptr_array(B), _ptr(q_out), _ptr(k_cache), _ptr(v_cache),
-                                     _ptr(slot_mapping), block_size, ctypes.byref(dims), _ptr(workspace),
+                                     _ptr(slot_mapping), block_size, ctypes.byref(dims), ctypes.byref(ex),
+                                     _ptr(workspace),
                                      workspace.numel() if workspace is not None else 0, ctypes.byref(h))
     if s:
         raise AloraError(s, "alora_qkv_graph_create")

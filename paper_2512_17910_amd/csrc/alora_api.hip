@@ -265,7 +265,8 @@ struct alora_graph {
 int alora_qkv_graph_create(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
                            const void *W_qkv, const void *const *A, const void *const *B, void *q_out,
                            void *k_cache, void *v_cache, const int64_t *slot_mapping, int32_t block_size,
-                           const alora_dims *dims, void *workspace, size_t workspace_bytes, alora_graph **out)
+                           const alora_dims *dims, const alora_extras *extras, void *workspace,
+                           size_t workspace_bytes, alora_graph **out)
 {
     if (!out) return ALORA_EINVAL;
     *out = nullptr;
@@ -277,7 +278,7 @@ int alora_qkv_graph_create(const void *x, const int32_t *token_adapter_ids, cons
     if (e) { (void)hipStreamDestroy(cs); g_last_hip_error = (int)e; return ALORA_EHIP; }
     // argument errors are found before anything is enqueued; the capture is ended either way
     const int status = forward_on(x, token_adapter_ids, activation_start, W_qkv, A, B, q_out, k_cache, v_cache,
-                                  slot_mapping, block_size, dims, workspace, workspace_bytes, cs, false);
+                                  slot_mapping, block_size, dims, workspace, workspace_bytes, cs, false, extras);
     hipGraph_t graph = nullptr;
     e = hipStreamEndCapture(cs, &graph);
     (void)hipStreamDestroy(cs);

@@ -124,3 +124,25 @@ def test_create_rejects_bad_arguments_without_leaving_a_capture_open():
     ab.alora_qkv_graph_launch(g)
     torch.cuda.synchronize()
     ab.alora_qkv_graph_destroy(g)
+
+
+def test_graph_with_bias_and_per_adapter_ranks():
+    w = wl.with_variants(_decode_step(7, 220, n_adapters=4, rank=32), ranks=(8, 32, 16, 24), bias=True)
+    static = DeviceBatch(w)
+    g = ab.alora_qkv_graph_create(static.x, static.aid, static.start, static.W, static.A, static.B, static.q,
+                                  static.kc, static.vc, static.slot, w.block_size, static.dims, static.ws,
+                                  bias=static.bias, adapter_ranks=w.adapter_ranks)
+    try:
+        ab.alora_qkv_graph_launch(g)
+        torch.cuda.synchronize()
+        eager = DeviceBatch(w)
+        eager.forward()
+        assert np.array_equal(raw_bits(static.q), raw_bits(eager.q))
+        assert np.array_equal(raw_bits(static.kc), raw_bits(eager.kc)) and np.array_equal(raw_bits(static.vc), raw_bits(eager.vc))
+        x, W, A, B = host_operands(w)
+        _, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+        rows = np.arange(w.T, dtype=np.int32)
+        y = oracle.alora_rows_var(x, W, A, B, w.token_adapter_ids, act, rows, wl.widen_f64(w.bias, w.dtype))
+        assert maxnorm_rel(to_f64(static.q), y[:, : w.Nq]) <= TOL[w.dtype]
+    finally:
+        ab.alora_qkv_graph_destroy(g)
