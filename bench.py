@@ -73,7 +73,8 @@ def main() -> int:
     graphs = []
     if args.graph:
         graphs = [ab.alora_qkv_graph_create(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot,
-                                            w.block_size, db.dims, db.ws) for (W, A, B) in copies]
+                                            w.block_size, db.dims, db.ws, bias=db.bias,
+                                            adapter_ranks=w.adapter_ranks) for (W, A, B) in copies]
 
     def step(i):
         if graphs:
