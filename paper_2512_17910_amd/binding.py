@@ -36,6 +36,13 @@ class AloraExtras(ctypes.Structure):
     _fields_ = [("bias", ctypes.c_void_p), ("adapter_ranks", ctypes.c_void_p)]
 
 
+class AloraAttnDims(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_tokens", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("n_seqs", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("block_size", ctypes.c_int32), ("n_slots", ctypes.c_int64),
+                ("scale", ctypes.c_float)]
+
+
 class AloraError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -70,6 +77,8 @@ def lib() -> ctypes.CDLL:
                                              ctypes.POINTER(vp)]
         L.alora_qkv_graph_launch.argtypes = [vp, vp]
         L.alora_qkv_graph_destroy.argtypes = [vp]
+        L.alora_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp]
+        L.alora_paged_attention_validate.argtypes = [vp, vp, vp, ctypes.POINTER(AloraAttnDims)]
         L.alora_status_string.argtypes = [ctypes.c_int]
         L.alora_status_string.restype = ctypes.c_char_p
         L.alora_qkv_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
@@ -78,7 +87,8 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
                      "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version",
-                     "alora_qkv_forward_ex", "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy"):
+                     "alora_qkv_forward_ex", "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy",
+                     "alora_paged_attention", "alora_paged_attention_validate"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -250,3 +260,24 @@ def alora_qkv_set_tuning(feature_tiles: int = 0, splits: int = 0) -> None:
     s = lib().alora_qkv_set_tuning(feature_tiles, splits)
     if s:
         raise AloraError(s, "alora_qkv_set_tuning")
+
+
+def make_attn_dims(q, k_cache, block_tables, n_q_heads: int, n_kv_heads: int, head_dim: int, block_size: int,
+                   scale: float = 0.0) -> AloraAttnDims:
+    """Dimensions of an alora_paged_attention call, read off the tensors."""
+    return AloraAttnDims(_dtype_code(q), q.shape[0], n_q_heads, n_kv_heads, head_dim, block_tables.shape[0],
+                         block_tables.shape[1], block_size, k_cache.shape[0], scale)
+
+
+def alora_paged_attention(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out,
+                          dims: AloraAttnDims, stream=None) -> None:
+    """Enqueue causal softmax attention of the rows of q over the paged cache (include/alora_attention.h)."""
+    s = lib().alora_paged_attention(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(token_seq_ids),
+                                    _ptr(token_positions), _ptr(out), ctypes.byref(dims), _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_paged_attention")
+
+
+def alora_paged_attention_validate(block_tables, token_seq_ids, token_positions, dims: AloraAttnDims) -> int:
+    return int(lib().alora_paged_attention_validate(_ptr(block_tables), _ptr(token_seq_ids), _ptr(token_positions),
+                                                    ctypes.byref(dims)))

@@ -7,6 +7,7 @@
 namespace alora {
 
 static thread_local int g_last_hip_error = 0;
+void note_hip_error(int hip_error) { g_last_hip_error = hip_error; }
 
 // Benchmark aid: HIP events around the dominant kernel (the projection GEMM) of each forward call.
 struct Profile {

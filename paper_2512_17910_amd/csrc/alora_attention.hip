@@ -1,0 +1,347 @@
+// Reader of the paged K/V cache: causal softmax attention of query rows over the cached keys and
+// values of their sequences (Sec. 2.1; formula and layout in alora_attention.h).
+//
+// One workgroup (4 wavefronts) per (query row, K/V head); the G = n_q_heads / n_kv_heads query heads
+// that share the K/V head are processed together, so every cached byte is loaded once per row.
+// The work is a stream of K and V rows (2 * head_dim elements per context position and K/V head)
+// against 4 * G * head_dim flops: memory-bound, so plain fp32 vector arithmetic, no LDS staging and
+// no matrix instructions.
+//
+// Lane layout: head_dim / 8 lanes share one context position, 8 consecutive elements (16 bytes of
+// bf16) each, so a wavefront's load instruction covers 64 / (head_dim / 8) positions with whole
+// contiguous head rows.  The partial dot products are summed over those lanes with DPP adds
+// (quad swaps, then half-row and row mirrors: every lane ends with the same bits).  Each lane
+// group keeps its own running (max, sum, weighted V) -- 16 or 32 independent streams per
+// workgroup -- rescaled once per U positions; the streams are merged in a fixed order at the end
+// (lane groups by shuffles, wavefronts through LDS), so the result does not depend on timing.
+#include "alora_internal.h"
+#include "alora_attention.h"
+#include <vector>
+
+namespace alora {
+
+struct AttnArgs {
+    const void *q, *kc, *vc;
+    const int32_t *bt, *seq, *pos;
+    void *out;
+    int T, Hq, Hkv, n_seqs, max_blocks, bs, bs_shift;
+    long long n_slots;
+    float scale_log2e;   // scale * log2(e): the softmax runs on powers of two
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+    return v + __int_as_float(o);
+}
+
+// sum over the LPP lanes that share a position; all of them receive it
+template <int LPP>
+__device__ __forceinline__ float group_sum(float v)
+{
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror: the other quad of the 8 lanes
+    if (LPP == 16) v = dpp_add<0x140>(v);   // row_mirror: the other half of the 16 lanes
+    return v;
+}
+
+// 8 consecutive elements of a cache or query row, as loaded
+template <bool BF16> struct Raw8;
+template <> struct Raw8<true> {
+    u32x4 v;
+    __device__ __forceinline__ void zero() { v = u32x4{0u, 0u, 0u, 0u}; }
+    __device__ __forceinline__ void load(const void *base, size_t elem) { v = *(const u32x4 *)((const bf16_t *)base + elem); }
+    __device__ __forceinline__ void widen(float f[8]) const
+    {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+};
+template <> struct Raw8<false> {
+    f32x4 a, b;
+    __device__ __forceinline__ void zero() { a = f32x4{0.f, 0.f, 0.f, 0.f}; b = a; }
+    __device__ __forceinline__ void load(const void *base, size_t elem)
+    {
+        a = *(const f32x4 *)((const float *)base + elem);
+        b = *(const f32x4 *)((const float *)base + elem + 4);
+    }
+    __device__ __forceinline__ void widen(float f[8]) const
+    {
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    }
+};
+
+constexpr float NEG_INF = -__builtin_inff();
+
+template <int D, int G, bool BF16>
+__global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
+{
+    constexpr int LPP = D / 8;     // lanes per context position
+    constexpr int PPW = 64 / LPP;  // positions per wavefront and step
+    constexpr int PPI = 4 * PPW;   // positions per workgroup and step
+    constexpr int U = 4;           // steps whose loads are in flight together
+
+    __shared__ float sm[4][G], sl[4][G];
+    __shared__ float sacc[4][G][D];
+
+    const int t = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int grp = lane / LPP, c = lane % LPP;
+
+    const int sq = a.seq[t], p = a.pos[t];
+    const long long cap = (long long)a.max_blocks * a.bs;
+    int n_ctx = 0;
+    if (sq >= 0 && sq < a.n_seqs && p >= 0) n_ctx = (int)(p + 1ll < cap ? p + 1ll : cap);
+    const int32_t *bt = a.bt + (size_t)(n_ctx ? sq : 0) * a.max_blocks;
+    const int Nkv = a.Hkv * D;
+    const size_t col = (size_t)hk * D + 8 * c;
+
+    float qf[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        Raw8<BF16> r;
+        r.load(a.q, ((size_t)t * a.Hq + (size_t)hk * G + g) * D + 8 * c);
+        r.widen(qf[g]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[g][e] *= a.scale_log2e;
+    }
+
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = NEG_INF;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    }
+
+    for (int j0 = 0; j0 < n_ctx; j0 += PPI * U) {
+        Raw8<BF16> kr[U], vr[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * PPI + wave * PPW + grp;
+            kr[u].zero();
+            vr[u].zero();
+            ok[u] = false;
+            if (j < n_ctx) {
+                const int bi = a.bs_shift >= 0 ? (j >> a.bs_shift) : (j / a.bs);
+                const int blk = bt[bi];
+                const long long slot = (long long)blk * a.bs + (j - bi * a.bs);
+                if (blk >= 0 && slot < a.n_slots) {
+                    ok[u] = true;
+                    kr[u].load(a.kc, (size_t)slot * Nkv + col);
+                    vr[u].load(a.vc, (size_t)slot * Nkv + col);
+                }
+            }
+        }
+        // scores (in units of log2)
+        float s[U][G];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[8];
+            kr[u].widen(kf);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qf[g][e], kf[e], d);
+                d = group_sum<LPP>(d);
+                s[u][g] = ok[u] ? d : NEG_INF;
+            }
+        }
+        // running softmax, rescaled once per U positions
+        float pw[U][G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float mx = s[0][g];
+#pragma unroll
+            for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][g]);
+            const float mn = fmaxf(m[g], mx);
+            const bool none = mn == NEG_INF;     // nothing seen yet by this lane group
+            const float corr = none ? 1.f : __builtin_amdgcn_exp2f(m[g] - mn);
+            float ls = l[g] * corr;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                pw[u][g] = none ? 0.f : __builtin_amdgcn_exp2f(s[u][g] - mn);
+                ls += pw[u][g];
+            }
+            l[g] = ls;
+            m[g] = mn;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float vf[8];
+            vr[u].widen(vf);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pw[u][g], vf[e], acc[g][e]);
+        }
+    }
+
+    // merge the lane groups of a wavefront (same chunk c, different positions)
+#pragma unroll
+    for (int off = LPP; off < 64; off <<= 1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float mo = __shfl_xor(m[g], off), lo = __shfl_xor(l[g], off);
+            const float mn = fmaxf(m[g], mo);
+            const bool none = mn == NEG_INF;
+            const float ca = none ? 1.f : __builtin_amdgcn_exp2f(m[g] - mn);
+            const float cb = none ? 0.f : __builtin_amdgcn_exp2f(mo - mn);
+            l[g] = l[g] * ca + lo * cb;
+            m[g] = mn;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float ao = __shfl_xor(acc[g][e], off);
+                acc[g][e] = acc[g][e] * ca + ao * cb;
+            }
+        }
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (c == 0) { sm[wave][g] = m[g]; sl[wave][g] = l[g]; }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sacc[wave][g][8 * c + e] = acc[g][e];
+        }
+    }
+    __syncthreads();
+
+    // merge the four wavefronts in fixed order and store
+    for (int idx = tid; idx < G * D; idx += 256) {
+        const int g = idx / D, dd = idx % D;
+        float M = sm[0][g];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) M = fmaxf(M, sm[w][g]);
+        float L = 0.f, o = 0.f;
+        if (M != NEG_INF) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = __builtin_amdgcn_exp2f(sm[w][g] - M);
+                L += sl[w][g] * f;
+                o += sacc[w][g][dd] * f;
+            }
+        }
+        const float y = L > 0.f ? o / L : 0.f;
+        const size_t at = ((size_t)t * a.Hq + (size_t)hk * G + g) * D + dd;
+        if (BF16) ((bf16_t *)a.out)[at] = (bf16_t)f32_to_bf16_bits(y);
+        else ((float *)a.out)[at] = y;
+    }
+}
+
+template <int D, int G>
+static void launch_dg(const AttnArgs &a, bool bf16, hipStream_t st)
+{
+    const dim3 grid((unsigned)a.T * (unsigned)a.Hkv);
+    if (bf16) hipLaunchKernelGGL((paged_attention_kernel<D, G, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((paged_attention_kernel<D, G, false>), grid, dim3(256), 0, st, a);
+}
+
+template <int D>
+static bool launch_d(const AttnArgs &a, int G, bool bf16, hipStream_t st)
+{
+    switch (G) {
+    case 1: launch_dg<D, 1>(a, bf16, st); return true;
+    case 2: launch_dg<D, 2>(a, bf16, st); return true;
+    case 4: launch_dg<D, 4>(a, bf16, st); return true;
+    case 8: launch_dg<D, 8>(a, bf16, st); return true;
+    }
+    return false;
+}
+
+static int check_dims(const alora_attn_dims *d)
+{
+    if (!d) return ALORA_EINVAL;
+    if (d->dtype != ALORA_F32 && d->dtype != ALORA_BF16) return ALORA_EINVAL;
+    if (d->n_tokens < 0 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_seqs < 0 || d->max_blocks < 0 ||
+        d->block_size < 1 || d->n_slots < 0 || !(d->scale >= 0.f))
+        return ALORA_EINVAL;
+    if (d->head_dim != 64 && d->head_dim != 128) return ALORA_ESHAPE;
+    if (d->n_q_heads % d->n_kv_heads) return ALORA_ESHAPE;
+    const int G = d->n_q_heads / d->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return ALORA_ESHAPE;
+    if ((long long)d->n_tokens * d->n_kv_heads > 0x7fffffffll) return ALORA_ESHAPE;
+    return ALORA_OK;
+}
+
+}  // namespace alora
+
+extern "C" {
+
+int alora_paged_attention(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                          const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
+                          const alora_attn_dims *dims, void *hip_stream)
+{
+    using namespace alora;
+    const int st = check_dims(dims);
+    if (st) return st;
+    if (dims->n_tokens == 0) return ALORA_OK;
+    if (!q || !k_cache || !v_cache || !block_tables || !token_seq_ids || !token_positions || !out) return ALORA_EINVAL;
+    if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) return ALORA_EINVAL;
+    if (((uintptr_t)block_tables | (uintptr_t)token_seq_ids | (uintptr_t)token_positions) & 3) return ALORA_EINVAL;
+    AttnArgs a;
+    a.q = q; a.kc = k_cache; a.vc = v_cache;
+    a.bt = block_tables; a.seq = token_seq_ids; a.pos = token_positions;
+    a.out = out;
+    a.T = dims->n_tokens; a.Hq = dims->n_q_heads; a.Hkv = dims->n_kv_heads;
+    a.n_seqs = dims->n_seqs; a.max_blocks = dims->max_blocks; a.bs = dims->block_size;
+    a.bs_shift = -1;
+    for (int sft = 0; sft < 31; ++sft)
+        if ((1 << sft) == dims->block_size) a.bs_shift = sft;
+    a.n_slots = dims->n_slots;
+    const float scale = dims->scale > 0.f ? dims->scale : 1.0f / sqrtf((float)dims->head_dim);
+    a.scale_log2e = scale * 1.4426950408889634f;
+    const bool bf16 = dims->dtype == ALORA_BF16;
+    const int G = dims->n_q_heads / dims->n_kv_heads;
+    const bool launched = dims->head_dim == 128 ? launch_d<128>(a, G, bf16, (hipStream_t)hip_stream)
+                                                : launch_d<64>(a, G, bf16, (hipStream_t)hip_stream);
+    if (!launched) return ALORA_ESHAPE;
+    const hipError_t e = hipGetLastError();
+    if (e) { note_hip_error((int)e); return ALORA_EHIP; }
+    return ALORA_OK;
+}
+
+int alora_paged_attention_validate(const int32_t *block_tables, const int32_t *token_seq_ids,
+                                   const int32_t *token_positions, const alora_attn_dims *dims)
+{
+    using namespace alora;
+    const int st = check_dims(dims);
+    if (st) return st;
+    if (dims->n_tokens == 0) return ALORA_OK;
+    if (!block_tables || !token_seq_ids || !token_positions) return ALORA_EINVAL;
+    const size_t T = (size_t)dims->n_tokens, nt = (size_t)dims->n_seqs * (size_t)dims->max_blocks;
+    std::vector<int32_t> seq(T), pos(T), bt(nt);
+    hipError_t e = hipDeviceSynchronize();
+    if (!e) e = hipMemcpy(seq.data(), token_seq_ids, T * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (!e) e = hipMemcpy(pos.data(), token_positions, T * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (!e && nt) e = hipMemcpy(bt.data(), block_tables, nt * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e) { note_hip_error((int)e); return ALORA_EHIP; }
+    const long long cap = (long long)dims->max_blocks * dims->block_size;
+    const long long n_blocks = dims->n_slots / dims->block_size;
+    std::vector<long long> reach((size_t)dims->n_seqs, -1);   // furthest position any row of the sequence reads
+    for (size_t t = 0; t < T; ++t) {
+        if (seq[t] < 0 || seq[t] >= dims->n_seqs) return ALORA_EDATA;
+        if (pos[t] < 0 || pos[t] >= cap) return ALORA_EDATA;
+        if (pos[t] > reach[(size_t)seq[t]]) reach[(size_t)seq[t]] = pos[t];
+    }
+    for (int s = 0; s < dims->n_seqs; ++s) {
+        if (reach[(size_t)s] < 0) continue;
+        const long long last = reach[(size_t)s] / dims->block_size;
+        for (long long b = 0; b <= last; ++b) {
+            const int32_t blk = bt[(size_t)s * dims->max_blocks + (size_t)b];
+            if (blk < 0 || blk >= n_blocks) return ALORA_EDATA;
+        }
+    }
+    return ALORA_OK;
+}
+
+}  // extern "C"

@@ -68,6 +68,9 @@ __device__ __forceinline__ int effective_adapter(const int32_t *aid, const int32
     return (pos[t] >= start[seg[t]]) ? a : -1;
 }
 
+// remember a failed HIP call for alora_last_hip_error() (per host thread)
+void note_hip_error(int hip_error);
+
 // launches (each returns the hipError_t of its launch as int)
 int launch_classify_group(const Fwd &f);
 int launch_shrink_f32(const Fwd &f, const PtrTable &A);

@@ -22,7 +22,7 @@ import numpy as np
 SEED = 0x2512_1791_0A10_4A5D  # one fixed 64-bit constant; streams select the array
 
 # stream ids (second half of the Philox key)
-_ST_X, _ST_W, _ST_A, _ST_B, _ST_STRUCT, _ST_SLOTS, _ST_CACHE, _ST_BIAS = 1, 2, 3, 4, 5, 6, 7, 8
+_ST_X, _ST_W, _ST_A, _ST_B, _ST_STRUCT, _ST_SLOTS, _ST_CACHE, _ST_BIAS, _ST_Q = 1, 2, 3, 4, 5, 6, 7, 8, 9
 
 
 # --------------------------------------------------------------------------------------
@@ -346,3 +346,82 @@ def small_mixed(dtype: str = "bf16", hidden: int = 256, n_q_heads: int = 4, n_kv
                     n_adapters, rank, block_size, segs,
                     [s.first_pos + s.n_tokens for s in segs], seed=SEED ^ seed,
                     extra_blocks=5, pad_rows=pads, x_std=x_std)
+
+
+# --------------------------------------------------------------------------------------
+# inputs of the cache reader (attention over the paged K/V cache)
+# --------------------------------------------------------------------------------------
+@dataclass
+class AttentionCase:
+    """Query rows, a paged K/V cache and the block tables to read it through.  Values only: no scores,
+    no softmax."""
+    name: str
+    dtype: str
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    block_size: int
+    q: np.ndarray              # [T, n_q_heads*head_dim] storage dtype
+    k_cache: np.ndarray        # [n_slots, n_kv_heads*head_dim]
+    v_cache: np.ndarray
+    block_tables: np.ndarray   # int32 [n_seqs, max_blocks], -1 past a sequence's blocks
+    token_seq_ids: np.ndarray  # int32 [T]
+    token_positions: np.ndarray  # int32 [T]
+    seq_lens: np.ndarray       # tokens cached per sequence (every row's position is below it)
+
+    @property
+    def T(self) -> int:
+        return int(self.token_seq_ids.shape[0])
+
+    @property
+    def context_bytes(self) -> int:
+        """K and V bytes the rows' contexts cover (each row reads positions 0..p of all K/V heads)."""
+        eb = 2 if self.dtype == "bf16" else 4
+        return int((self.token_positions.astype(np.int64) + 1).sum()) * 2 * self.n_kv_heads * self.head_dim * eb
+
+
+def block_tables_of(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
+    """(block_tables int32 [n_seq, max_blocks], token_seq_ids int32 [T]) of a Workload: the sequence of a
+    row is the sequence of its segment."""
+    tabs = w._tables
+    mb = max(len(t) for t in tabs)
+    bt = np.full((len(tabs), mb), -1, np.int32)
+    for s, t in enumerate(tabs):
+        bt[s, :len(t)] = t
+    seq_of_seg = np.asarray([sg.seq for sg in w.segments], np.int32)
+    return bt, seq_of_seg[w.token_seg_ids]
+
+
+def attention_case(name: str, dtype: str, seq_lens: Sequence[int], rows_per_seq: Sequence[int], n_q_heads: int,
+                   n_kv_heads: int, head_dim: int, block_size: int, seed: int = SEED, extra_blocks: int = 2,
+                   table_slack: int = 1, kv_std: float = 1.0) -> AttentionCase:
+    """Sequence s holds seq_lens[s] cached tokens; its last rows_per_seq[s] positions are query rows (a
+    decode step has one, a projected suffix several).  Physical blocks are a seeded permutation; slots
+    no context covers (spare blocks, tails of last blocks) hold NaN so that a read of them shows."""
+    lens = np.asarray(seq_lens, np.int64)
+    nb = (lens + block_size - 1) // block_size
+    n_blocks = int(nb.sum()) + extra_blocks
+    perm = _rng(seed, _ST_SLOTS, 1).permutation(n_blocks)
+    bt = np.full((len(lens), int(nb.max()) + table_slack), -1, np.int32)
+    covered = np.zeros(n_blocks * block_size, bool)
+    o = 0
+    for s in range(len(lens)):
+        bt[s, :nb[s]] = perm[o:o + nb[s]]
+        j = np.arange(lens[s])
+        covered[perm[o:o + nb[s]][j // block_size] * block_size + j % block_size] = True
+        o += int(nb[s])
+    seq, pos = [], []
+    for s in range(len(lens)):
+        r = int(min(rows_per_seq[s], lens[s]))
+        seq += [s] * r
+        pos += list(range(int(lens[s]) - r, int(lens[s])))
+    width = n_kv_heads * head_dim
+    kc = _normal(seed, _ST_CACHE, 10, (n_blocks * block_size, width), kv_std, "f32")
+    vc = _normal(seed, _ST_CACHE, 11, (n_blocks * block_size, width), kv_std, "f32")
+    kc[~covered] = np.nan
+    vc[~covered] = np.nan
+    q = _normal(seed, _ST_Q, 0, (len(seq), n_q_heads * head_dim), 1.0, dtype)
+    if dtype == "bf16":
+        kc, vc = f32_to_bf16_bits(kc), f32_to_bf16_bits(vc)
+    return AttentionCase(name, dtype, n_q_heads, n_kv_heads, head_dim, block_size, q, kc, vc, bt,
+                         np.asarray(seq, np.int32), np.asarray(pos, np.int32), lens)

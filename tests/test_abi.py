@@ -110,3 +110,35 @@ def test_forward_rejects_bad_arguments_before_any_launch():
     assert call(x=None, aid=None, W=None, q=None, slot=None, dims=_dims(T=0)) == ab.ALORA_OK
     assert L.alora_status_string(ab.ALORA_ESHAPE).decode().startswith("unsupported shape")
     assert L.alora_qkv_version() >= 100
+
+
+def _attn_dims(**kw):
+    d = dict(dtype=ab.ALORA_BF16, n_tokens=8, n_q_heads=8, n_kv_heads=2, head_dim=128, n_seqs=2, max_blocks=4,
+             block_size=16, n_slots=128, scale=0.0)
+    d.update(kw)
+    return ab.AloraAttnDims(**d)
+
+
+def test_paged_attention_argument_checks_answer_on_the_host():
+    L = ab.lib()
+    p = lambda v: ctypes.c_void_p(v)
+    good = [p(0x1000), p(0x2000), p(0x3000), p(0x4000), p(0x5000), p(0x6000), p(0x7000)]
+    call = lambda args, d: L.alora_paged_attention(*args, ctypes.byref(d), None)
+    assert call(good, _attn_dims(head_dim=96)) == ab.ALORA_ESHAPE
+    assert call(good, _attn_dims(n_q_heads=6)) == ab.ALORA_ESHAPE           # 3 query heads per K/V head
+    assert call(good, _attn_dims(n_q_heads=7)) == ab.ALORA_ESHAPE
+    assert call(good, _attn_dims(block_size=0)) == ab.ALORA_EINVAL
+    assert call(good, _attn_dims(dtype=5)) == ab.ALORA_EINVAL
+    assert call(good, _attn_dims(scale=-1.0)) == ab.ALORA_EINVAL
+    assert call(good, _attn_dims(scale=float("nan"))) == ab.ALORA_EINVAL
+    assert call(good, _attn_dims(n_tokens=0)) == ab.ALORA_OK                 # nothing to do, nothing launched
+    for i in range(7):
+        args = list(good)
+        args[i] = p(None)
+        assert call(args, _attn_dims()) == ab.ALORA_EINVAL
+    args = list(good)
+    args[0] = p(0x1008)                                                       # q not 16-byte aligned
+    assert call(args, _attn_dims()) == ab.ALORA_EINVAL
+    assert L.alora_paged_attention(*good, None, None) == ab.ALORA_EINVAL
+    assert L.alora_paged_attention_validate(p(0x4000), p(0x5000), p(0x6000), ctypes.byref(_attn_dims(head_dim=32))) == ab.ALORA_ESHAPE
+    assert ctypes.sizeof(ab.AloraAttnDims) == 48

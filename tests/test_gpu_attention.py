@@ -1,0 +1,180 @@
+"""GPU parity of the paged-cache reader (alora_paged_attention) against the fp64 oracle
+(oracle/attention.py: causal softmax attention, Sec. 2.1), through the C ABI.
+
+Slots no context covers hold NaN in every case, so a read outside a row's causal context shows up
+as a NaN in the output."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oatt
+from paper_2512_17910_amd import binding as ab
+from paper_2512_17910_amd import workloads as wl
+from gpu_util import TOL, maxnorm_rel, raw_bits, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+class DeviceCase:
+    def __init__(self, c: wl.AttentionCase, scale: float = 0.0):
+        self.c = c
+        self.q = to_dev(c.q, c.dtype)
+        self.kc = to_dev(c.k_cache, c.dtype)
+        self.vc = to_dev(c.v_cache, c.dtype)
+        self.bt = torch.from_numpy(c.block_tables).to("cuda")
+        self.seq = torch.from_numpy(c.token_seq_ids).to("cuda")
+        self.pos = torch.from_numpy(c.token_positions).to("cuda")
+        self.out = torch.full_like(self.q, float("nan"))
+        self.dims = ab.make_attn_dims(self.q, self.kc, self.bt, c.n_q_heads, c.n_kv_heads, c.head_dim, c.block_size, scale)
+
+    def run(self):
+        ab.alora_paged_attention(self.q, self.kc, self.vc, self.bt, self.seq, self.pos, self.out, self.dims)
+        torch.cuda.synchronize()
+        return self.out
+
+    def oracle(self, rows=None, scale=None):
+        c = self.c
+        return oatt.paged_attention(wl.widen_f64(c.q, c.dtype), wl.widen_f64(c.k_cache, c.dtype),
+                                    wl.widen_f64(c.v_cache, c.dtype), c.block_tables, c.token_seq_ids,
+                                    c.token_positions, c.block_size, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                                    scale=scale, rows=rows)
+
+
+def _ragged_lens(seed, n, hi):
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(1, hi + 1, n)
+    lens[0] = 1                       # a context of one position
+    lens[1] = hi
+    return lens
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("head_dim", [64, 128])
+@pytest.mark.parametrize("group", [1, 2, 4, 8])
+def test_matches_the_oracle_on_ragged_contexts(dtype, head_dim, group):
+    n_kv = 2
+    lens = _ragged_lens(100 + group + head_dim, 9, 333)
+    rows = [1, 3, 1, 2, 1, 5, 1, 1, 4]
+    for bs in (16, 5):                # a power of two and not
+        c = wl.attention_case(f"ragged-{dtype}-d{head_dim}-g{group}-bs{bs}", dtype, lens, rows, n_kv * group, n_kv,
+                              head_dim, bs, seed=wl.SEED ^ (head_dim * 8 + group))
+        print(f"[case] {c.name} T={c.T} lens={list(lens)}", flush=True)
+        d = DeviceCase(c)
+        assert ab.alora_paged_attention_validate(d.bt, d.seq, d.pos, d.dims) == ab.ALORA_OK
+        out = to_f64(d.run())
+        assert np.isfinite(out).all()
+        assert maxnorm_rel(out, d.oracle()) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_long_contexts_and_explicit_scale(dtype):
+    lens = [5000, 4097, 4096, 63, 64, 65, 1023]
+    c = wl.attention_case(f"long-{dtype}", dtype, lens, [2, 1, 1, 1, 1, 1, 1], 8, 2, 128, 16, seed=wl.SEED ^ 77)
+    print(f"[case] {c.name}", flush=True)
+    d = DeviceCase(c, scale=0.05)
+    out = to_f64(d.run())
+    assert np.isfinite(out).all()
+    assert maxnorm_rel(out, d.oracle(scale=0.05)) <= TOL[dtype]
+
+
+def test_peaked_scores_do_not_overflow():
+    """Large score ranges: keys scaled so that scores span hundreds; the running maximum keeps every power
+    of two in range."""
+    c = wl.attention_case("peaked", "bf16", [700, 300, 40], [1, 2, 3], 4, 1, 128, 16, seed=wl.SEED ^ 5, kv_std=6.0)
+    d = DeviceCase(c)
+    out = to_f64(d.run())
+    assert np.isfinite(out).all()
+    assert maxnorm_rel(out, d.oracle()) <= TOL["bf16"]
+
+
+def test_rows_of_one_sequence_see_exactly_their_causal_context():
+    """A projected suffix: 40 consecutive rows of one sequence.  Changing the cached K/V of position j
+    changes rows at positions >= j and leaves the rows before it bit-identical."""
+    c = wl.attention_case("suffix", "bf16", [200, 90], [40, 1], 8, 2, 64, 16, seed=wl.SEED ^ 9)
+    d = DeviceCase(c)
+    base = raw_bits(d.run()).copy()
+    assert maxnorm_rel(to_f64(d.out), d.oracle()) <= TOL["bf16"]
+    j = 180                                             # row index 20 of the suffix (positions 160..199)
+    slot = int(c.block_tables[0][j // 16]) * 16 + j % 16
+    d.vc[slot] += 1.0
+    d.kc[slot] *= -1.0
+    after = raw_bits(d.run())
+    rows_before = np.flatnonzero((c.token_seq_ids == 0) & (c.token_positions < j))
+    rows_after = np.flatnonzero((c.token_seq_ids == 0) & (c.token_positions >= j))
+    assert rows_before.size == 20 and rows_after.size == 20
+    assert np.array_equal(after[rows_before], base[rows_before])
+    assert all((after[r] != base[r]).any() for r in rows_after)
+    other = np.flatnonzero(c.token_seq_ids == 1)
+    assert np.array_equal(after[other], base[other])
+
+
+def test_two_calls_give_the_same_bits_and_the_stream_argument_is_honoured():
+    c = wl.attention_case("repeat", "bf16", _ragged_lens(3, 40, 900), [1] * 40, 32, 8, 128, 16, seed=wl.SEED ^ 21)
+    d = DeviceCase(c)
+    first = raw_bits(d.run()).copy()
+    d.out.fill_(float("nan"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    ab.alora_paged_attention(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, stream=side)
+    side.synchronize()
+    assert np.array_equal(raw_bits(d.out), first)
+
+
+def test_out_of_range_indices_are_reported_and_never_dereferenced():
+    c = wl.attention_case("bad-indices", "bf16", [50, 60, 70], [1, 1, 1], 4, 2, 64, 16, seed=wl.SEED ^ 33)
+    d = DeviceCase(c)
+    good = to_f64(d.run()).copy()
+    n_blocks = c.k_cache.shape[0] // 16
+    # a sequence id outside the table, a negative position: rows of zeros
+    seq = c.token_seq_ids.copy()
+    seq[0] = 7
+    pos = c.token_positions.copy()
+    pos[1] = -3
+    d.seq.copy_(torch.from_numpy(seq))
+    d.pos.copy_(torch.from_numpy(pos))
+    assert ab.alora_paged_attention_validate(d.bt, d.seq, d.pos, d.dims) == ab.ALORA_EDATA
+    out = to_f64(d.run())
+    assert (out[0] == 0).all() and (out[1] == 0).all()
+    assert np.array_equal(out[2], good[2])
+    # table entries outside the cache inside a context: those positions are left out of the softmax
+    d.seq.copy_(torch.from_numpy(c.token_seq_ids))
+    d.pos.copy_(torch.from_numpy(c.token_positions))
+    bt = c.block_tables.copy()
+    bt[2, 1] = n_blocks + 5          # positions 16..31 of sequence 2
+    bt[2, 3] = -1                    # positions 48..63
+    d.bt.copy_(torch.from_numpy(bt))
+    assert ab.alora_paged_attention_validate(d.bt, d.seq, d.pos, d.dims) == ab.ALORA_EDATA
+    out = to_f64(d.run())
+    assert np.isfinite(out).all()
+    keep = np.r_[0:16, 32:48, 64:70]
+    kc, vc = wl.widen_f64(c.k_cache, "bf16"), wl.widen_f64(c.v_cache, "bf16")
+    slots = oatt.context_slots(c.block_tables[2], 70, 16)[keep]
+    dense_bt = np.arange((len(keep) + 15) // 16, dtype=np.int32)[None, :]
+    kd = np.zeros((dense_bt.size * 16, kc.shape[1])); kd[:len(keep)] = kc[slots]
+    vd = np.zeros((dense_bt.size * 16, vc.shape[1])); vd[:len(keep)] = vc[slots]
+    ref = oatt.paged_attention(wl.widen_f64(c.q, "bf16")[2:3], kd, vd, dense_bt, np.zeros(1, np.int32),
+                               np.asarray([len(keep) - 1], np.int32), 16, 4, 2, 64)
+    assert maxnorm_rel(out[2:3], ref) <= TOL["bf16"]
+    assert np.array_equal(out[:2], good[:2])
+
+
+def test_empty_batch_is_a_no_op():
+    c = wl.attention_case("empty", "bf16", [20], [1], 4, 2, 64, 16, seed=wl.SEED ^ 41)
+    d = DeviceCase(c)
+    dims = ab.make_attn_dims(d.q[:0], d.kc, d.bt, 4, 2, 64, 16)
+    ab.alora_paged_attention(d.q[:0], d.kc, d.vc, d.bt, d.seq[:0], d.pos[:0], d.out[:0], dims)
+    torch.cuda.synchronize()
+    assert torch.isnan(d.out).all()
+
+
+def test_decode_batch_at_benchmark_size_on_sampled_rows():
+    """The reader's benchmark configuration (256 decode rows, 32 query / 8 K/V heads of 128, contexts up
+    to 2048): every row finite, 24 sampled rows against the oracle."""
+    rng = np.random.default_rng(8)
+    lens = rng.integers(2, 2049, 256)
+    c = wl.attention_case("decode-256", "bf16", lens, [1] * 256, 32, 8, 128, 16, seed=wl.SEED ^ 55)
+    d = DeviceCase(c)
+    out = to_f64(d.run())
+    assert np.isfinite(out).all()
+    rows = np.r_[np.argmax(lens), np.argmin(lens), rng.choice(256, 22, replace=False)]
+    assert maxnorm_rel(out[rows], d.oracle(rows=rows)) <= TOL["bf16"]
