@@ -140,3 +140,83 @@ def test_alora_turn_reuses_base_blocks_and_the_cache_matches_a_from_scratch_orac
     # a standard LoRA (activation at 0) shares nothing
     b = pl.Batch(256, 4)
     assert planner.admit(5, conv, 2, 0, b) == 0
+
+
+def _attend(m: TinyModel, planner, rid, q, positions):
+    """The reader over request rid's block table for rows at `positions` (their q from the projection)."""
+    table = np.asarray(planner.block_table(rid), np.int32)[None, :]
+    bt = torch.from_numpy(table).to("cuda")
+    seq = torch.zeros(len(positions), dtype=torch.int32, device="cuda")
+    pos = torch.from_numpy(np.asarray(positions, np.int32)).to("cuda")
+    out = torch.empty_like(q)
+    dims = ab.make_attn_dims(q, m.kc, bt, NQH, NKVH, HD, BS)
+    assert ab.alora_paged_attention_validate(bt, seq, pos, dims) == ab.ALORA_OK
+    ab.alora_paged_attention(q, m.kc, m.vc, bt, seq, pos, out, dims)
+    torch.cuda.synchronize()
+    return to_f64(out)
+
+
+def _dense_attention(m: TinyModel, tokens, adapter, start, positions):
+    """The whole conversation from scratch in fp64: projection of every token (adapter applied from the
+    activation point on), then causal attention over the dense K and V."""
+    from oracle import attention as oatt
+    n = len(tokens)
+    x = wl.widen_f64(m.emb_host[np.asarray(tokens)], m.dtype)
+    W = wl.widen_f64(m.W_host, m.dtype)
+    A = [wl.widen_f64(a, m.dtype) for a in m.A_host]
+    B = [wl.widen_f64(b, m.dtype) for b in m.B_host]
+    aid = np.full(n, adapter, np.int32)
+    _, act = oracle.classify(aid, np.zeros(n, np.int32), np.arange(n, dtype=np.int32), np.asarray([start], np.int32))
+    y = oracle.alora_rows(x, W, A, B, aid, act, np.arange(n, dtype=np.int32))
+    q, k, v = y[:, :NQ], y[:, NQ:NQ + NKV], y[:, NQ + NKV:]
+    nb = (n + BS - 1) // BS
+    pad = lambda a: np.vstack([a, np.zeros((nb * BS - n, a.shape[1]))])
+    return oatt.paged_attention(q, pad(k), pad(v), np.arange(nb, dtype=np.int32)[None, :], np.zeros(n, np.int32),
+                                np.arange(n, dtype=np.int32), BS, NQH, NKVH, HD, rows=np.asarray(positions))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_over_reused_blocks_matches_a_dense_from_scratch_computation(dtype):
+    """Sec. 2.3's claim in numbers: an aLoRA request whose first 64 positions were written by a base-model
+    request's projection, the rest by its own (adapted from the activation point on), attends over both
+    and gets what a dense computation of its whole sequence gives; the same for a base request that
+    continues the conversation over the shared blocks."""
+    rng = np.random.default_rng(6)
+    m = TinyModel(dtype)
+    planner = pl.Planner(BS, N_BLOCKS)
+    prompt = [int(t) for t in rng.integers(0, VOCAB, 75)]
+    invocation = [int(t) for t in rng.integers(0, VOCAB, 5)]
+    # two chained steps (projection, then attention), each within the single-step gate
+    tol = 2 * TOL[dtype]
+
+    b = pl.Batch(256, 4)
+    assert planner.admit(1, prompt, -1, NEVER, b) == 0
+    q1 = m.forward(b, prompt)
+    planner.commit(1)
+    got = _attend(m, planner, 1, q1, list(range(75)))
+    assert maxnorm_rel(got, _dense_attention(m, prompt, -1, NEVER, list(range(75)))) <= tol
+    planner.finish(1)
+
+    conv = prompt + invocation
+    start = len(prompt)
+    b = pl.Batch(256, 4)
+    cached = planner.admit(2, conv, 1, start, b)
+    assert cached == 64
+    q2 = m.forward(b, conv[cached:])                       # rows for positions 64..79 only
+    planner.commit(2)
+    positions = list(range(cached, len(conv)))
+    got = _attend(m, planner, 2, q2, positions)
+    ref = _dense_attention(m, conv, 1, start, positions)
+    assert maxnorm_rel(got, ref) <= tol
+    # the adapter matters: the same rows computed as a base request differ by far more than the gate
+    assert maxnorm_rel(_dense_attention(m, conv, -1, NEVER, positions)[start - cached:], ref[start - cached:]) > 10 * tol
+
+    # the base model continues over the same conversation and shares the four pre-activation blocks
+    b = pl.Batch(256, 4)
+    assert planner.admit(3, conv, -1, NEVER, b) == 64
+    q3 = m.forward(b, conv[64:])
+    planner.commit(3)
+    got = _attend(m, planner, 3, q3, positions)
+    assert maxnorm_rel(got, _dense_attention(m, conv, -1, NEVER, positions)) <= tol
+    # and request 2's view is unchanged by request 3's writes
+    assert maxnorm_rel(_attend(m, planner, 2, q2, positions), ref) <= tol
