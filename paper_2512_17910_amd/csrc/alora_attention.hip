@@ -78,13 +78,36 @@ template <> struct Raw8<false> {
 
 constexpr float NEG_INF = -__builtin_inff();
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// <q chunk, k chunk> over 8 elements.  bf16: four packed two-element dot products on the stored bits
+// (fp32 accumulate); fp32: eight FMAs.  The pairs are taken with shufflevector on the 8-element vector:
+// bit casts of the single 32-bit words were compiled into four uses of the first word by this toolchain.
+__device__ __forceinline__ float dot8(const Raw8<true> &q, const Raw8<true> &k)
+{
+    const bf16x8 qv = __builtin_bit_cast(bf16x8, q.v), kv = __builtin_bit_cast(bf16x8, k.v);
+    float d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(qv, qv, 0, 1), __builtin_shufflevector(kv, kv, 0, 1), 0.f, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(qv, qv, 2, 3), __builtin_shufflevector(kv, kv, 2, 3), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(qv, qv, 4, 5), __builtin_shufflevector(kv, kv, 4, 5), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(qv, qv, 6, 7), __builtin_shufflevector(kv, kv, 6, 7), d, false);
+    return d;
+}
+__device__ __forceinline__ float dot8(const Raw8<false> &q, const Raw8<false> &k)
+{
+    float d = q.a.x * k.a.x;
+    d = fmaf(q.a.y, k.a.y, d); d = fmaf(q.a.z, k.a.z, d); d = fmaf(q.a.w, k.a.w, d);
+    d = fmaf(q.b.x, k.b.x, d); d = fmaf(q.b.y, k.b.y, d); d = fmaf(q.b.z, k.b.z, d); d = fmaf(q.b.w, k.b.w, d);
+    return d;
+}
+
 template <int D, int G, bool BF16>
 __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
 {
-    constexpr int LPP = D / 8;     // lanes per context position
-    constexpr int PPW = 64 / LPP;  // positions per wavefront and step
-    constexpr int PPI = 4 * PPW;   // positions per workgroup and step
-    constexpr int U = 4;           // steps whose loads are in flight together
+    constexpr int LPP = D / 8;         // lanes per context position
+    constexpr int PPW = 64 / LPP;      // positions per wavefront and step
+    constexpr int PPI = 4 * PPW;       // positions per workgroup and step
+    constexpr int U = BF16 ? 4 : 2;    // steps per block: loaded together, one rescale of the running sums
+    constexpr int BLK = PPI * U;       // positions per workgroup and block
 
     __shared__ float sm[4][G], sl[4][G];
     __shared__ float sacc[4][G][D];
@@ -100,16 +123,11 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     const int32_t *bt = a.bt + (size_t)(n_ctx ? sq : 0) * a.max_blocks;
     const int Nkv = a.Hkv * D;
     const size_t col = (size_t)hk * D + 8 * c;
+    const int jl = wave * PPW + grp;   // this lane group's position inside a step
 
-    float qf[G][8];
+    Raw8<BF16> qr[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        Raw8<BF16> r;
-        r.load(a.q, ((size_t)t * a.Hq + (size_t)hk * G + g) * D + 8 * c);
-        r.widen(qf[g]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[g][e] *= a.scale_log2e;
-    }
+    for (int g = 0; g < G; ++g) qr[g].load(a.q, ((size_t)t * a.Hq + (size_t)hk * G + g) * D + 8 * c);
 
     float m[G], l[G], acc[G][8];
 #pragma unroll
@@ -120,42 +138,41 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
         for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
     }
 
-    for (int j0 = 0; j0 < n_ctx; j0 += PPI * U) {
-        Raw8<BF16> kr[U], vr[U];
-        bool ok[U];
+    // block-table entries of the block starting at j0 (-1 past the context)
+    auto lookup = [&](int j0, int (&blk)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int j = j0 + u * PPI + wave * PPW + grp;
+            const int j = j0 + u * PPI + jl;
+            blk[u] = -1;
+            if (j < n_ctx) blk[u] = bt[a.bs_shift >= 0 ? (j >> a.bs_shift) : (j / a.bs)];
+        }
+    };
+    // K and V chunks of the block starting at j0, through table entries looked up earlier
+    auto fetch = [&](int j0, const int (&blk)[U], Raw8<BF16> (&kr)[U], Raw8<BF16> (&vr)[U], bool (&ok)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * PPI + jl;
+            const int bi = a.bs_shift >= 0 ? (j >> a.bs_shift) : (j / a.bs);
+            const long long slot = (long long)blk[u] * a.bs + (j - bi * a.bs);
             kr[u].zero();
             vr[u].zero();
-            ok[u] = false;
-            if (j < n_ctx) {
-                const int bi = a.bs_shift >= 0 ? (j >> a.bs_shift) : (j / a.bs);
-                const int blk = bt[bi];
-                const long long slot = (long long)blk * a.bs + (j - bi * a.bs);
-                if (blk >= 0 && slot < a.n_slots) {
-                    ok[u] = true;
-                    kr[u].load(a.kc, (size_t)slot * Nkv + col);
-                    vr[u].load(a.vc, (size_t)slot * Nkv + col);
-                }
+            ok[u] = blk[u] >= 0 && slot < a.n_slots;   // blk is -1 past the context
+            if (ok[u]) {
+                kr[u].load(a.kc, (size_t)slot * Nkv + col);
+                vr[u].load(a.vc, (size_t)slot * Nkv + col);
             }
         }
-        // scores (in units of log2)
-        float s[U][G];
+    };
+    // scores, running softmax (rescaled once per block) and weighted sum of V for one block
+    auto consume = [&](const Raw8<BF16> (&kr)[U], const Raw8<BF16> (&vr)[U], const bool (&ok)[U]) {
+        float s[U][G];   // in units of log2
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[8];
-            kr[u].widen(kf);
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                float d = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) d = fmaf(qf[g][e], kf[e], d);
-                d = group_sum<LPP>(d);
-                s[u][g] = ok[u] ? d : NEG_INF;
+                const float d = group_sum<LPP>(dot8(qr[g], kr[u]));
+                s[u][g] = ok[u] ? d * a.scale_log2e : NEG_INF;
             }
-        }
-        // running softmax, rescaled once per U positions
         float pw[U][G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -184,6 +201,25 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
             for (int g = 0; g < G; ++g)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pw[u][g], vf[e], acc[g][e]);
+        }
+    };
+
+    // Two register sets: while one block is consumed the next block's K/V loads and the table entries
+    // of the block after it are in flight.
+    int blkA[U], blkB[U];
+    Raw8<BF16> krA[U], vrA[U], krB[U], vrB[U];
+    bool okA[U], okB[U];
+    lookup(0, blkA);
+    fetch(0, blkA, krA, vrA, okA);
+    lookup(BLK, blkB);
+    for (int j0 = 0; j0 < n_ctx; j0 += 2 * BLK) {
+        fetch(j0 + BLK, blkB, krB, vrB, okB);
+        lookup(j0 + 2 * BLK, blkA);
+        consume(krA, vrA, okA);
+        if (j0 + BLK < n_ctx) {
+            fetch(j0 + 2 * BLK, blkA, krA, vrA, okA);
+            lookup(j0 + 3 * BLK, blkB);
+            consume(krB, vrB, okB);
         }
     }
 
