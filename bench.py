@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="replay the call as a HIP graph (alora_qkv_graph_*), one graph per rotated weight copy; the "
                          "kernel-level roofline figures then come from rocprofv3, not from in-call events")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="context, not part of the path: also time the vendor library's plain bf16 GEMM x @ W of the "
+                         "same shape (torch.matmul: no adapters, no mask, no cache scatter) on the same box")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known size) so that a rocprofv3 --pmc run of this "
                          "command holds a reference dispatch for the FETCH_SIZE / WRITE_SIZE counters")
@@ -192,6 +195,19 @@ def main() -> int:
         # parity of the timed GPU result on the same sample
         q = to_f64(db.q[torch.from_numpy(rows.astype(np.int64)).to("cuda")])
         out["parity_sample_max_rel_err_q"] = maxnorm_rel(q, y[:, : w.Nq])
+    if args.library_gemm:
+        o = torch.empty((w.T, w.N), dtype=db.x.dtype, device="cuda")
+        for i in range(args.warmup):
+            torch.matmul(db.x, copies[i % rotate][0], out=o)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            torch.matmul(db.x, copies[i % rotate][0], out=o)
+        e1.record()
+        torch.cuda.synchronize()
+        lib_ms = e0.elapsed_time(e1) / args.steps
+        out["library_plain_gemm"] = {"what": "torch.matmul(x, W_qkv), bf16, same shape and box; no adapters, mask or scatter",
+                                     "us": lib_ms * 1e3, "tflops": 2.0 * w.T * w.hidden * w.N / (lib_ms * 1e-3) / 1e12}
     for g in graphs:
         ab.alora_qkv_graph_destroy(g)
     print(json.dumps(out))
