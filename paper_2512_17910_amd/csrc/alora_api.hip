@@ -20,8 +20,8 @@ static Profile g_prof;
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t active, aeff, perm, offsets, S, blocktab, hist, partial, total;
-    int n_blocks;
+    size_t active, aeff, perm, offsets, S, blocktab, items, counters, hist, partial, total;
+    int n_blocks, n_items;
 };
 
 static int check_dims(const alora_dims *d)
@@ -61,6 +61,9 @@ static Layout make_layout(const alora_dims *d)
     l.S = o;       o += up256(T * r * 4 * (d->dtype == ALORA_BF16 ? (size_t)ALORA_SHRINK_MAX_SPLITS : 1));
     l.n_blocks = group_blocks(d->T, d->n_adapters);
     l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
+    l.n_items = d->dtype == ALORA_BF16 ? shrink_items(d->T, d->n_adapters) : 0;
+    l.items = o;    o += up256(16 * (size_t)l.n_items);
+    l.counters = o; o += up256(4 * (size_t)(l.n_items ? l.n_blocks : 0));
     l.hist = o;     o += up256(group_hist_bytes(d->T));
     l.partial = o;
     if (d->dtype == ALORA_BF16) o += up256(gemm_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
@@ -91,6 +94,11 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
     f.S = b + l.S;
     f.blocktab = (int4 *)(b + l.blocktab);
     f.hist = (int32_t *)(b + l.hist);
+    const int N_all = (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim;
+    const bool work_list = d->dtype == ALORA_BF16 && plan_shrink(d->T, d->hidden, N_all, d->n_adapters, d->rank).combine;
+    f.items = work_list ? (int4 *)(b + l.items) : nullptr;
+    f.counters = work_list ? (int32_t *)(b + l.counters) : nullptr;
+    f.n_items = work_list ? l.n_items : 0;
     f.partial = (float *)(b + l.partial);
     f.n_blocks = l.n_blocks;
     f.stream = (hipStream_t)stream;

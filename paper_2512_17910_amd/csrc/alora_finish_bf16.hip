@@ -138,7 +138,7 @@ static void launch_finish(const Fwd &f, const PtrTable &B)
 {
     const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
     hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
-                       f.S, plan_shrink(f.T, f.H, f.N, f.L).splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
+                       f.S, plan_shrink(f.T, f.H, f.N, f.L, f.r).splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
                        (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
 }
 

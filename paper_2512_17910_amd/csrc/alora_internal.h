@@ -45,6 +45,12 @@ struct Fwd {
     int32_t *hist;       // large batches: rows per (2048-row slice, group), see the grouping kernels
     int4 *blocktab;      // shrink: (adapter, first perm index, rows, 0) per 32-row block; adapter -1 = unused
     int n_blocks;        // entries in blocktab (upper bound on 32-row blocks)
+    // prefill-sized bf16 batches: the shrink's work list, one item per (32-row block of an adapter, range
+    // of the hidden dimension), written by the grouping step from the number of adapted blocks it finds;
+    // null when the shrink walks blocktab instead
+    int4 *items;         // (adapter, first perm index, rows | range width/64 << 8, range | ranges << 4 | block << 8)
+    int32_t *counters;   // per block: ranges that have stored their partial (zeroed by the grouping step)
+    int n_items;
     hipStream_t stream;
 };
 
@@ -89,10 +95,22 @@ void set_gemm_tuning(int ntw, int splits);
 int group_blocks(int T, int L);
 size_t group_hist_bytes(int T);
 constexpr int ALORA_SHRINK_MAX_SPLITS = 8;
+constexpr int ALORA_SHRINK_TARGET_WGS = 256;   // workgroups the prefill-sized shrink aims for (one per compute unit)
 struct ShrinkPlan {
     int splits;  // ranges of the hidden dimension; the shrink result is the fixed-order sum of their partials
     int kper;    // width of one range (multiple of 64)
+    // Prefill-sized batches: the number of ranges is chosen on the device, per call, from the number of
+    // adapted 32-row blocks (at most `splits`); the last range of a block to finish adds the partials in
+    // fixed order and stores the (hi, lo) form.  The shrink then walks Fwd::items.
+    bool combine;
 };
-ShrinkPlan plan_shrink(int T, int H, int N, int L);
+// what the grouping kernels need to write the shrink's work list
+struct ShrinkWork {
+    int4 *items;
+    int32_t *counters;
+    int n_items, k64, rmax;
+};
+int shrink_items(int T, int L);   // entries of the work list
+ShrinkPlan plan_shrink(int T, int H, int N, int L, int r);
 
 }  // namespace alora

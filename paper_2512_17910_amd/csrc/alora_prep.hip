@@ -12,6 +12,7 @@
 // wavefront-local cursors.  Ranks inside a 64-row step come from ballots, so there are no
 // data-dependent atomics and the result is deterministic.  Batches of 6144 rows or more take the
 // two-launch, many-workgroup form further down.
+#include <algorithm>
 #include "alora_internal.h"
 
 namespace alora {
@@ -21,12 +22,45 @@ constexpr int PREP_THREADS = PREP_WAVES * 64;
 constexpr int PREP_CACHE_ROWS = 96 * 1024;     // one byte per row
 constexpr int NKEYS = ALORA_MAX_ADAPTERS + 1;  // adapters + the base group
 
+// Work list of the prefill-sized bf16 shrink.  Adapted rows fill the first bfirst[L] entries of the
+// block table; each of those blocks is cut into `eff` ranges of the hidden dimension so that about
+// ALORA_SHRINK_TARGET_WGS workgroups come out (never more than rmax ranges, none empty).  Item i is
+// range i % eff of block i / eff; the rest of the list is marked unused.  The per-block counters of
+// finished ranges start at zero.  Entries first, first + stride, ... are written by the caller.
+__device__ __forceinline__ void emit_shrink_items(const ShrinkWork &sw, int L, const int *goff, const int *bfirst,
+                                                  const int *tot, int n_blocks, int first, int stride)
+{
+    if (!sw.items) return;
+    const int nab = bfirst[L];
+    int eff = 1, kper64 = sw.k64;
+    if (nab > 0) {
+        eff = max(1, min(sw.rmax, ALORA_SHRINK_TARGET_WGS / nab));
+        kper64 = (sw.k64 + eff - 1) / eff;
+        eff = (sw.k64 + kper64 - 1) / kper64;
+    }
+    for (int i = first; i < sw.n_items; i += stride) {
+        int4 v = make_int4(-1, 0, 0, 0);
+        if (i < nab * eff) {
+            const int e = i / eff, rg = i - e * eff;
+            int lo = 0, hi = L;  // smallest group whose blocks end after e
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (bfirst[mid + 1] > e) hi = mid; else lo = mid + 1;
+            }
+            const int b = e - bfirst[lo];
+            v = make_int4(lo, goff[lo] + 32 * b, min(32, tot[lo] - 32 * b) | (kper64 << 8), rg | (eff << 4) | (e << 8));
+        }
+        sw.items[i] = v;
+    }
+    for (int i = first; i < n_blocks; i += stride) sw.counters[i] = 0;
+}
+
 template <bool CACHED>
 __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
     const int32_t *__restrict__ aid, const int32_t *__restrict__ seg, const int32_t *__restrict__ pos,
     const int32_t *__restrict__ start, int T, int L, uint8_t *__restrict__ active,
     int8_t *__restrict__ aeff_out, int32_t *__restrict__ perm, int32_t *__restrict__ offsets,
-    int4 *__restrict__ blocktab, int n_blocks)
+    int4 *__restrict__ blocktab, int n_blocks, ShrinkWork sw)
 {
     __shared__ int cnt[PREP_WAVES][NKEYS];
     __shared__ int goff[3 * 64 + 1], bfirst[3 * 64 + 1], tot[3 * 64];
@@ -168,6 +202,7 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_group_kernel(
         }
         blocktab[e] = v;
     }
+    emit_shrink_items(sw, L, goff, bfirst, tot, n_blocks, threadIdx.x, PREP_THREADS);
 
     // pass 2: placement
     for (int tb = t0; tb < t1; tb += 64) {
@@ -266,7 +301,7 @@ __global__ __launch_bounds__(PREP_THREADS) void classify_slices_kernel(
 
 __global__ __launch_bounds__(PREP_THREADS) void place_slices_kernel(
     const int8_t *__restrict__ aeff_in, const int32_t *__restrict__ hist, int T, int L, int32_t *__restrict__ perm,
-    int32_t *__restrict__ offsets, int4 *__restrict__ blocktab, int n_blocks)
+    int32_t *__restrict__ offsets, int4 *__restrict__ blocktab, int n_blocks, ShrinkWork sw)
 {
     __shared__ int cnt[PREP_WAVES][NKEYS];
     __shared__ int goff[3 * 64 + 1], bfirst[3 * 64 + 1], tot[3 * 64], slice_base[NKEYS];
@@ -345,6 +380,8 @@ __global__ __launch_bounds__(PREP_THREADS) void place_slices_kernel(
         }
         blocktab[e] = v;
     }
+    emit_shrink_items(sw, L, goff, bfirst, tot, n_blocks, (int)blockIdx.x * PREP_THREADS + threadIdx.x,
+                      (int)gridDim.x * PREP_THREADS);
     // placement
     const unsigned long long lanes_below = (1ull << lane) - 1ull;
     int *my_cnt = cnt[w];
@@ -367,20 +404,24 @@ int group_blocks(int T, int L) { return (T + 31) / 32 + L + 1; }
 constexpr int PREP_TWO_LAUNCH_FROM = 6144;
 size_t group_hist_bytes(int T) { return T >= PREP_TWO_LAUNCH_FROM ? (size_t)((T + PREP_SLICE - 1) / PREP_SLICE) * NKEYS * 4 : 0; }
 
+int shrink_items(int T, int L) { return std::max(group_blocks(T, L), ALORA_SHRINK_TARGET_WGS); }
+
 int launch_classify_group(const Fwd &f)
 {
     if (f.T == 0) return 0;
+    ShrinkWork sw = {nullptr, nullptr, 0, 0, 0};
+    if (f.items) sw = ShrinkWork{f.items, f.counters, f.n_items, f.H / 64, plan_shrink(f.T, f.H, f.N, f.L, f.r).splits};
     if (f.T >= PREP_TWO_LAUNCH_FROM) {
         const int slices = (f.T + PREP_SLICE - 1) / PREP_SLICE;
         hipLaunchKernelGGL(classify_slices_kernel, dim3(slices), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg, f.pos,
                            f.start, f.T, f.L, f.active, f.aeff, f.hist);
         hipLaunchKernelGGL(place_slices_kernel, dim3(slices), dim3(PREP_THREADS), 0, f.stream, (const int8_t *)f.aeff,
-                           (const int32_t *)f.hist, f.T, f.L, f.perm, f.offsets, f.blocktab, f.n_blocks);
+                           (const int32_t *)f.hist, f.T, f.L, f.perm, f.offsets, f.blocktab, f.n_blocks, sw);
         return (int)hipGetLastError();
     }
     static_assert(PREP_TWO_LAUNCH_FROM <= PREP_CACHE_ROWS, "smaller batches fit the single workgroup's LDS row cache");
     hipLaunchKernelGGL(classify_group_kernel<true>, dim3(1), dim3(PREP_THREADS), 0, f.stream, f.aid, f.seg, f.pos,
-                       f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks);
+                       f.start, f.T, f.L, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks, sw);
     return (int)hipGetLastError();
 }
 

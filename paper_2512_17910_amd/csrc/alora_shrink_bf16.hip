@@ -12,14 +12,17 @@
 // the end.
 //
 // Two forms of the result, chosen by the host with the projection's plan:
-//   - one range (prefill-sized batches, enough row blocks to fill the chip): the fp32 result is
-//     handed on as two bf16 numbers per element, S = hi + lo with hi = bf16(S), lo = bf16(S - hi),
-//     stored as [hi_0..hi_{r-1} | lo_0..lo_{r-1}] per row: the projection kernel runs the expand on
-//     the same bf16 MFMA pipe as the base GEMM ([S_hi | S_lo] against [B ; B]) and still sees ~16
-//     mantissa bits of S;
-//   - several ranges (small batches, a handful of row blocks that would each be latency-bound over
-//     the whole hidden dimension): every range leaves an fp32 partial P[range][t][:], and the
-//     finishing kernel adds the ranges in fixed order.
+//   - prefill-sized batches (fused projection kernel): the fp32 result is handed on as two bf16
+//     numbers per element, S = hi + lo with hi = bf16(S), lo = bf16(S - hi), stored as
+//     [hi_0..hi_{r-1} | lo_0..lo_{r-1}] per row: the projection kernel runs the expand on the same
+//     bf16 MFMA pipe as the base GEMM ([S_hi | S_lo] against [B ; B]) and still sees ~16 mantissa
+//     bits of S.  The workgroups walk a work list the grouping step wrote: with few adapted blocks
+//     every block is cut into ranges of the hidden dimension (one workgroup each, about one per
+//     compute unit in all); a range stores its fp32 partial, and the LAST range of a block to
+//     finish (a counter per block) adds the block's partials in range order and stores (hi, lo) --
+//     the sum does not depend on which range came last;
+//   - small batches (split projection + finishing kernel): every range leaves an fp32 partial
+//     P[range][t][:], and the finishing kernel adds the ranges in fixed order.
 #include <algorithm>
 #include "alora_internal.h"
 
@@ -34,11 +37,13 @@ __device__ __attribute__((aligned(256))) uint32_t g_zero_page[64];  // zero-init
 constexpr int SHRINK_ROWS = 32;
 
 // KSL: hidden-dimension chunk per LDS buffer; NT: 32-wide rank tiles (1 for rank <= 32, else 2)
-template <int KSL, int NT>
+// WORK_LIST: walk the (block, range) items of the grouping step and combine the ranges of a block
+// here; otherwise walk the block table with blockIdx.y as the range.
+template <int KSL, int NT, bool WORK_LIST>
 __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restrict__ x, PtrTable A, RankTable ranks,
                                                           const int32_t *__restrict__ perm,
-                                                          const int4 *__restrict__ blocktab, int L, int H, int r, uint32_t x_bytes,
-                                                          int T, int kper, void *__restrict__ S_out)
+                                                          const int4 *__restrict__ blocktab, int32_t *counters, int L, int H,
+                                                          int r, uint32_t x_bytes, int T, int kper, void *S_out)
 {
     constexpr int XROW_BYTES = KSL * 2;
     constexpr int CPR = KSL / 8;                 // 16-byte chunks per token row
@@ -56,10 +61,13 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
 
     // which (adapter, 32-row block) is this workgroup?  (table written by the grouping kernel)
     const int4 entry = blocktab[blockIdx.x];
-    const int a = entry.x, j0 = entry.y, cnt = entry.z;
+    const int a = entry.x, j0 = entry.y, cnt = WORK_LIST ? (entry.z & 0xff) : entry.z;
     if (a < 0 || a >= L) return;  // unused entry or the base group; uniform across the workgroup
-    // this workgroup's range of the hidden dimension (the host sizes gridDim.y so that none is empty)
-    const int kbeg = (int)blockIdx.y * kper, kend = min(H, kbeg + kper);
+    // this workgroup's range of the hidden dimension (sized so that none is empty)
+    const int range = WORK_LIST ? (entry.w & 15) : (int)blockIdx.y;
+    const int n_ranges = WORK_LIST ? ((entry.w >> 4) & 15) : (int)gridDim.y;
+    if (WORK_LIST) kper = (entry.z >> 8) * 64;
+    const int kbeg = range * kper, kend = min(H, kbeg + kper);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -193,7 +201,25 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
     __syncthreads();
 
     // ---- add the four wavefronts in fixed order; store (hi, lo) or this range's fp32 partial -----
-    const bool ranges = gridDim.y > 1;
+    const bool ranges = n_ranges > 1, ranges_gt1 = ranges;
+    // Work-list mode with several ranges: everything that crosses workgroups inside this kernel (the
+    // partials, the counter, and the (hi, lo) rows that reuse the bytes of range 0's partials) goes
+    // through device-scope relaxed atomics, i.e. loads and stores that bypass the per-XCD L2's
+    // non-coherent lines; no cache-wide write-back or invalidate is needed (a device-scope fence
+    // flushes the whole L2 under the other workgroups' reads of x and A: measured 3x slower).
+    const bool coherent = WORK_LIST && ranges_gt1;
+    auto store_hi_lo = [&](int tt, int col, float s) {
+        const uint32_t hi = f32_to_bf16_bits(s);
+        const uint32_t lo = f32_to_bf16_bits(s - bf16_bits_to_f32(hi));
+        bf16_t *dst = (bf16_t *)S_out + (size_t)tt * 2 * r;
+        if (coherent) {
+            __hip_atomic_store(dst + col, (bf16_t)hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + r + col, (bf16_t)lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            dst[col] = (bf16_t)hi;
+            dst[r + col] = (bf16_t)lo;
+        }
+    };
     for (int idx = tid; idx < 32 * 32 * NT; idx += 256) {
         const int col = idx % (32 * NT), row = idx / (32 * NT);
         const int tt = rows_t[row];
@@ -201,25 +227,71 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
         const int nt = col >> 5, c = col & 31;
         // rank columns past this adapter's own rank are zero (the consumers walk the common rank r)
         const float s = col < rk ? ((red[0][nt][row][c] + red[1][nt][row][c]) + red[2][nt][row][c]) + red[3][nt][row][c] : 0.f;
-        if (ranges) {
-            ((float *)S_out)[((size_t)blockIdx.y * T + tt) * r + col] = s;
-        } else {
-            const uint32_t hi = f32_to_bf16_bits(s);
-            const uint32_t lo = f32_to_bf16_bits(s - bf16_bits_to_f32(hi));
-            bf16_t *dst = (bf16_t *)S_out + (size_t)tt * 2 * r;
-            dst[col] = (bf16_t)hi;
-            dst[r + col] = (bf16_t)lo;
+        float *part = (float *)S_out + ((size_t)range * T + tt) * r + col;
+        if (coherent) __hip_atomic_store(part, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else if (ranges) *part = s;
+        else store_hi_lo(tt, col, s);
+    }
+    if (!WORK_LIST || !ranges) return;
+
+    // ---- the last range of this block to get here adds the block's partials and stores (hi, lo) ----
+    // The partial of range 0 of a row and the row's (hi, lo) form occupy the same 4r bytes, so every
+    // partial of the block is read before the first (hi, lo) store.
+    __shared__ int is_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's partials have been written through
+    __syncthreads();
+    if (tid == 0)
+        is_last = __hip_atomic_fetch_add(&counters[entry.w >> 8], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_ranges - 1;
+    __syncthreads();
+    if (!is_last) return;
+    constexpr int PER = 32 * 32 * NT / 256;
+    // all loads first (they are round trips past the L2), then the sums in range order
+    float part[PER][ALORA_SHRINK_MAX_SPLITS], sum[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int idx = tid + 256 * k, col = idx % (32 * NT), tt = rows_t[idx / (32 * NT)];
+#pragma unroll
+        for (int g = 0; g < ALORA_SHRINK_MAX_SPLITS; ++g) {
+            part[k][g] = 0.f;
+            if (tt >= 0 && col < r && g < n_ranges)
+                part[k][g] = __hip_atomic_load((const float *)S_out + ((size_t)g * T + tt) * r + col, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        float sv = 0.f;
+#pragma unroll
+        for (int g = 0; g < ALORA_SHRINK_MAX_SPLITS; ++g) sv += part[k][g];   // ranges past n_ranges add +0
+        sum[k] = sv;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int idx = tid + 256 * k, col = idx % (32 * NT), tt = rows_t[idx / (32 * NT)];
+        if (tt >= 0 && col < r) store_hi_lo(tt, col, sum[k]);
     }
 }
 
-// Ranges of the hidden dimension the shrink is cut into.  Only the small-batch path (split
-// projection + finishing kernel) uses more than one: about 512 workgroups' worth of row blocks at
-// most, never more than 8 ranges, each a multiple of 64 wide and none empty.
-ShrinkPlan plan_shrink(int T, int H, int N, int L)
+// Ranges of the hidden dimension the shrink is cut into, never more than 8, each a multiple of 64 wide
+// and none empty.  Small-batch path (split projection + finishing kernel): fixed by the host, about 512
+// workgroups' worth of row blocks at most.  Prefill-sized path: one range unless a block's loads are large
+// (wide hidden dimension, high rank); then `splits` is the upper limit (ranges at least 512 wide) and the
+// grouping step picks the number per call from the adapted blocks it finds.
+ShrinkPlan plan_shrink(int T, int H, int N, int L, int r)
 {
-    ShrinkPlan p = {1, H};
-    if (T <= 0 || L <= 0 || plan_gemm(T, H, N).splits == 1) return p;
+    ShrinkPlan p = {1, H, false};
+    if (T <= 0 || L <= 0) return p;
+    if (plan_gemm(T, H, N).splits == 1) {
+        // Cutting a block into ranges adds a chain of round trips past the L2 (partials written through,
+        // counter, partials read back: about 6 us); it pays once a block's 32 token rows and its adapter's
+        // A, all pulled through one compute unit, take clearly longer than that (0.5 MB is about 11 us).
+        if ((size_t)(SHRINK_ROWS + r) * H * 2 >= (768u << 10)) {
+            p.splits = std::max(1, std::min(ALORA_SHRINK_MAX_SPLITS, H / 512));
+            p.combine = p.splits > 1;
+        }
+        return p;
+    }
     const int want = std::max(1, std::min(ALORA_SHRINK_MAX_SPLITS, 512 / group_blocks(T, L)));
     const int k64 = H / 64;
     p.kper = ((k64 + want - 1) / want) * 64;
@@ -227,17 +299,26 @@ ShrinkPlan plan_shrink(int T, int H, int N, int L)
     return p;
 }
 
+template <int KSL, int NT>
+static void launch_shrink(const Fwd &f, const PtrTable &A, const ShrinkPlan &sp)
+{
+    const uint32_t x_bytes = (uint32_t)((size_t)f.T * f.H * 2);
+    if (sp.combine)
+        hipLaunchKernelGGL((shrink_bf16_kernel<KSL, NT, true>), dim3(f.n_items), dim3(256), 0, f.stream, (const bf16_t *)f.x, A,
+                           f.ranks, f.perm, (const int4 *)f.items, f.counters, f.L, f.H, f.r, x_bytes, f.T, 0, f.S);
+    else
+        hipLaunchKernelGGL((shrink_bf16_kernel<KSL, NT, false>), dim3(f.n_blocks, sp.splits), dim3(256), 0, f.stream,
+                           (const bf16_t *)f.x, A, f.ranks, f.perm, (const int4 *)f.blocktab, (int32_t *)nullptr, f.L, f.H, f.r,
+                           x_bytes, f.T, sp.kper, f.S);
+}
+
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;
-    const ShrinkPlan sp = plan_shrink(f.T, f.H, f.N, f.L);
-    const dim3 grid(f.n_blocks, sp.splits);
-    if (f.r <= 32)
-        hipLaunchKernelGGL((shrink_bf16_kernel<512, 1>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.ranks, f.perm,
-                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), f.T, sp.kper, f.S);
-    else
-        hipLaunchKernelGGL((shrink_bf16_kernel<256, 2>), grid, dim3(256), 0, f.stream, (const bf16_t *)f.x, A, f.ranks, f.perm,
-                           f.blocktab, f.L, f.H, f.r, (uint32_t)((size_t)f.T * f.H * 2), f.T, sp.kper, f.S);
+    const ShrinkPlan sp = plan_shrink(f.T, f.H, f.N, f.L, f.r);
+    if (sp.combine && !f.items) return (int)hipErrorInvalidValue;
+    if (f.r <= 32) launch_shrink<512, 1>(f, A, sp);
+    else launch_shrink<256, 2>(f, A, sp);
     return (int)hipGetLastError();
 }
 

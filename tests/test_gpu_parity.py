@@ -303,3 +303,32 @@ def test_forward_ex_rejects_bad_ranks():
                                     w.block_size, db.dims, db.ws, adapter_ranks=bad)
         assert e.value.status == ab.ALORA_ESHAPE
     assert np.array_equal(raw_bits(db.kc), raw_bits(db.k0))
+
+
+@pytest.mark.parametrize("variant", ["common-rank", "per-adapter-ranks"])
+def test_wide_hidden_high_rank_shrink_cuts_blocks_into_ranges_and_combines_them_in_the_kernel(tuning, variant):
+    """hidden 8192 with rank 64: a 32-row block's loads are large enough that the prefill-sized shrink cuts
+    it into ranges of the hidden dimension, the last range of a block to finish adding the partials.
+    The fused projection is forced (the batch is small), the result matches the oracle, and two calls
+    give the same bits whichever range finishes last."""
+    w = wl.small_mixed("bf16", seed=21, hidden=8192, rank=64, n_adapters=3, seq_lens=(300, 41, 1, 77, 130, 64),
+                       pad_every=23)
+    if variant == "per-adapter-ranks":
+        w = wl.with_variants(w, ranks=(64, 8, 40), bias=True)
+    for ft in (2, 4):
+        tuning(ft, 1)
+        if variant == "common-rank":
+            db, _ = _check_full(w)
+        else:
+            db = DeviceBatch(w)
+            db.forward()
+            x, W, A, B = host_operands(w)
+            _, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+            y = oracle.alora_rows_var(x, W, A, B, w.token_adapter_ids, act, np.arange(w.T, dtype=np.int32),
+                                      wl.widen_f64(w.bias, w.dtype))
+            assert maxnorm_rel(to_f64(db.q), y[:, : w.Nq]) <= TOL["bf16"]
+        first = (raw_bits(db.q).copy(), raw_bits(db.kc).copy(), raw_bits(db.vc).copy())
+        for _ in range(3):
+            db.reset()
+            db.forward()
+            assert all(np.array_equal(a, b) for a, b in zip(first, (raw_bits(db.q), raw_bits(db.kc), raw_bits(db.vc))))
