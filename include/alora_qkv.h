@@ -217,6 +217,9 @@ int alora_qkv_set_tuning(int feature_tiles, int splits);
  */
 int alora_qkv_profile_begin(int max_calls);
 int alora_qkv_profile_end(double *avg_ms, int *n_calls);
+/* The same, measuring only every `every`-th call (>= 1): an event pair costs a few microseconds
+ * of stream time, which shows in the step time of decode-sized calls. */
+int alora_qkv_profile_begin_every(int max_calls, int every);
 
 /* Static description of a status code. */
 const char *alora_status_string(int status);

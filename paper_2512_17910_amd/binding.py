@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
         L.alora_qkv_set_tuning.restype = ctypes.c_int
         L.alora_qkv_profile_begin.argtypes = [ctypes.c_int]
+        L.alora_qkv_profile_begin_every.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.alora_qkv_profile_begin_every.restype = ctypes.c_int
         L.alora_qkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
                      "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version",
@@ -240,8 +242,9 @@ def alora_qkv_validate(token_adapter_ids, activation_start, slot_mapping, block_
                                         block_size, ctypes.byref(dims)))
 
 
-def alora_qkv_profile_begin(max_calls: int) -> None:
-    s = lib().alora_qkv_profile_begin(max_calls)
+def alora_qkv_profile_begin(max_calls: int, every: int = 1) -> None:
+    """Measure the dominant kernel of every `every`-th forward call, at most max_calls of them."""
+    s = lib().alora_qkv_profile_begin_every(max_calls, every)
     if s:
         raise AloraError(s, "alora_qkv_profile_begin")
 

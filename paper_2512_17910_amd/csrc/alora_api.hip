@@ -13,6 +13,7 @@ void note_hip_error(int hip_error) { g_last_hip_error = hip_error; }
 struct Profile {
     bool on = false;
     int used = 0;
+    int every = 1, seen = 0;   // every `every`-th call is measured
     std::vector<hipEvent_t> ev0, ev1;
 };
 static Profile g_prof;
@@ -227,7 +228,8 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
     f.x = x; f.W = W_qkv; f.aid = token_adapter_ids; f.start = activation_start; f.slot = slot_mapping;
     f.q = q_out; f.kc = k_cache; f.vc = v_cache;
 
-    const bool timed = allow_timing && g_prof.on && g_prof.used < (int)g_prof.ev0.size();
+    bool timed = allow_timing && g_prof.on && g_prof.used < (int)g_prof.ev0.size();
+    if (timed) timed = (g_prof.seen++ % g_prof.every) == 0;
     int e = launch_classify_group(f);
     if (!e) {
         if (f.dtype == ALORA_F32) {
@@ -333,9 +335,11 @@ int alora_qkv_set_tuning(int feature_tiles, int splits)
     return ALORA_OK;
 }
 
-int alora_qkv_profile_begin(int max_calls)
+int alora_qkv_profile_begin(int max_calls) { return alora_qkv_profile_begin_every(max_calls, 1); }
+
+int alora_qkv_profile_begin_every(int max_calls, int every)
 {
-    if (max_calls <= 0 || max_calls > (1 << 20)) return ALORA_EINVAL;
+    if (max_calls <= 0 || max_calls > (1 << 20) || every < 1) return ALORA_EINVAL;
     if (g_prof.on) return ALORA_EINVAL;
     g_prof.ev0.assign((size_t)max_calls, nullptr);
     g_prof.ev1.assign((size_t)max_calls, nullptr);
@@ -345,6 +349,8 @@ int alora_qkv_profile_begin(int max_calls)
         if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
     }
     g_prof.used = 0;
+    g_prof.every = every;
+    g_prof.seen = 0;
     g_prof.on = true;
     return ALORA_OK;
 }
