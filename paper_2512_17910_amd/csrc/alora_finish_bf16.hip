@@ -67,7 +67,13 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
             for (int j = c; j < ra; j += 32) {
                 float sj = 0.f;
                 if (s_splits > 1) {
-                    for (int ks = 0; ks < s_splits; ++ks) sj += S_part[((size_t)ks * T + t) * r + j];
+                    // all ranges' loads first, then the sum in range order (absent ranges add +0)
+                    float sp[ALORA_SHRINK_MAX_SPLITS];
+#pragma unroll
+                    for (int ks = 0; ks < ALORA_SHRINK_MAX_SPLITS; ++ks)
+                        sp[ks] = ks < s_splits ? S_part[((size_t)ks * T + t) * r + j] : 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < ALORA_SHRINK_MAX_SPLITS; ++ks) sj += sp[ks];
                 } else {
                     const bf16_t *row = (const bf16_t *)S_part + (size_t)t * 2 * r;
                     sj = bf16_bits_to_f32(row[j]) + bf16_bits_to_f32(row[r + j]);
