@@ -136,9 +136,10 @@ def main() -> int:
     act_rank = float(sum(rk[int(a)] for a in w.token_adapter_ids[act == 1]))   # sum of the active rows' ranks
     flops = 2.0 * w.T * w.hidden * w.N + 2.0 * act_rank * w.N
     if args.config == 3:
-        # small-batch path: the dominant kernel is the split projection, which streams x and W;
-        # adapters, rounding and the stores belong to the finishing kernel
-        bytes_ = e * (w.T * w.hidden + w.hidden * w.N)
+        # small-batch path: the dominant kernel is the split projection, which streams x and W and, on
+        # workgroups of its own, groups the batch and shrinks the adapted rows (their x rows again, the used
+        # adapters' A, the fp32 shrink result out); B, rounding and the stores belong to the finishing kernel
+        bytes_ = e * (w.T * w.hidden + w.hidden * w.N + T_act * w.hidden + used * w.hidden * w.rank) + T_act * w.rank * 4
     else:
         bytes_ = e * (w.T * w.hidden + w.hidden * w.N + used * w.rank * w.N + T_act * 2 * w.rank
                       + w.T * w.Nq + T_w * 2 * w.Nkv) + w.T * (1 + 8)

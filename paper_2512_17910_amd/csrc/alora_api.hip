@@ -230,7 +230,9 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
 
     bool timed = allow_timing && g_prof.on && g_prof.used < (int)g_prof.ev0.size();
     if (timed) timed = (g_prof.seen++ % g_prof.every) == 0;
-    int e = launch_classify_group(f);
+    // decode-sized bf16 batches: grouping and shrink ride in the projection kernel (two launches in all)
+    const bool prep_inside = prep_in_projection(f);
+    int e = prep_inside ? 0 : launch_classify_group(f);
     if (!e) {
         if (f.dtype == ALORA_F32) {
             e = launch_shrink_f32(f, ta);
@@ -238,11 +240,11 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
             if (!e) e = launch_gemm_f32(f, tb);
             if (!e && timed) e = (int)hipEventRecord(g_prof.ev1[g_prof.used], f.stream);
         } else {
-            e = launch_shrink_bf16(f, ta);
+            if (!prep_inside) e = launch_shrink_bf16(f, ta);
             if (!e && timed) e = (int)hipEventRecord(g_prof.ev0[g_prof.used], f.stream);
             // the second event is recorded right behind the projection kernel (before the finishing
             // kernel of the small-batch path)
-            if (!e) e = launch_gemm_bf16(f, tb, timed ? g_prof.ev1[g_prof.used] : nullptr);
+            if (!e) e = launch_gemm_bf16(f, tb, ta, timed ? g_prof.ev1[g_prof.used] : nullptr);
         }
         if (!e && timed) g_prof.used++;
     }

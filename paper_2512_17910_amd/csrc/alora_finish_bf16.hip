@@ -140,24 +140,24 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
 }
 
 template <int SPLITS>
-static void launch_finish(const Fwd &f, const PtrTable &B)
+static void launch_finish(const Fwd &f, const PtrTable &B, int s_splits)
 {
     const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
     hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
-                       f.S, plan_shrink(f.T, f.H, f.N, f.L, f.r).splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
+                       f.S, s_splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
                        (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
 }
 
-int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits)
+int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits)
 {
     switch (splits) {
-    case 2: launch_finish<2>(f, B); break;
-    case 3: launch_finish<3>(f, B); break;
-    case 4: launch_finish<4>(f, B); break;
-    case 5: launch_finish<5>(f, B); break;
-    case 6: launch_finish<6>(f, B); break;
-    case 7: launch_finish<7>(f, B); break;
-    case 8: launch_finish<8>(f, B); break;
+    case 2: launch_finish<2>(f, B, s_splits); break;
+    case 3: launch_finish<3>(f, B, s_splits); break;
+    case 4: launch_finish<4>(f, B, s_splits); break;
+    case 5: launch_finish<5>(f, B, s_splits); break;
+    case 6: launch_finish<6>(f, B, s_splits); break;
+    case 7: launch_finish<7>(f, B, s_splits); break;
+    case 8: launch_finish<8>(f, B, s_splits); break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();

@@ -31,6 +31,8 @@
 //     per-lane condition and stores are 8-byte vectors.
 #include <algorithm>
 #include "alora_internal.h"
+#include "alora_group_small.h"
+#include "alora_shrink_rows.h"
 
 namespace alora {
 
@@ -58,6 +60,12 @@ struct GemmArgs {
     float *partial;   // split mode: [splits][T][N] fp32
     const bf16_t *bias;   // [N] or null: added to every row before rounding (fused mode)
     RankTable ranks;      // per adapter: B_a has ranks.r[a] rows
+    // split mode: the grid is one-dimensional, tiles8 workgroups per split, followed by `prep_wgs`
+    // workgroups that classify, group and shrink the batch (0: separate kernels did that)
+    int tiles8, splits, prep_wgs;
+    int prep_ranges, prep_kper;   // ranges of the hidden dimension per block-table entry, and their width
+    GroupSmallArgs prep;
+    void *S_out;          // shrink result written by the prep workgroups ((hi, lo) form)
 };
 
 // Buffer descriptor of a raw byte buffer (stride 0, 32-bit data format): offsets at or past
@@ -93,11 +101,11 @@ __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p, int pitch)
 }
 
 // NTW: 32-wide feature tiles per wavefront; the workgroup tile is 256 tokens x 64*NTW features.
-// SPLIT: small-batch mode.  blockIdx.y selects a range of K-slices; the kernel only accumulates the
+// SPLIT: small-batch mode.  The workgroup index selects a tile and a range of K-slices; the kernel only accumulates the
 // base product over that range and stores the fp32 accumulators to g.partial[split][T][N]; adapters,
 // rounding and the q_out / cache stores are left to the finishing kernel.
 template <int NTW, bool SPLIT>
-__global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B)
+__global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B, PtrTable A)
 {
     constexpr int BN = 64 * NTW;
     // Ring geometry.  128-feature tiles keep weight rows of 256 bytes, which makes a stage 24 KB and
@@ -134,10 +142,41 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // own L2: XCD k = blockIdx.x % 8 takes a contiguous range of a tile order that walks panels of
     // 4 token tiles, feature tile by feature tile, so that the ~32 tiles an XCD runs at a time form
     // a 4 x 8 patch sharing their token and weight slices in that L2.
+    // split mode: blockIdx.x = split * tiles8 + tile, then the prep workgroups (dispatched last, so
+    // that they take the compute units the projection leaves free)
+    int bx = (int)blockIdx.x, by = 0;
+    if (SPLIT) {
+        by = bx / g.tiles8;
+        bx -= by * g.tiles8;
+        if (by >= g.splits) {
+            if constexpr (SPLIT && NTW == 2) {
+                // One entry of the 32-row block table: group the batch, then the shrink of the block over
+                // the whole hidden dimension, out of this kernel's stages (token buffers, A buffers,
+                // reduction array, scratch).
+                static_assert(STAGE_BYTES >= (uint32_t)ShrinkLds<256, 1>::X_BYTES && STAGE_BYTES >= (uint32_t)ShrinkLds<256, 1>::A_BYTES &&
+                              STAGE_BYTES >= (uint32_t)ShrinkLds<256, 1>::RED_BYTES && STAGE_BYTES >= (GROUP_SMALL_SCRATCH + 4) * 4u,
+                              "stages hold the shrink's buffers");
+                // prep_ranges workgroups per entry, one per range of the hidden dimension; each works the
+                // grouping out for itself, the first of them writes the entry's share of its results
+                const int p = (int)blockIdx.x - g.tiles8 * g.splits;
+                const int e = p / g.prep_ranges, range = p - e * g.prep_ranges;
+                int *scr = (int *)stage5;
+                int grp, cnt;
+                const int *rows = group_small(g.prep, g.T, g.L, e, range == 0, scr, grp, cnt);
+                if (grp < 0 || grp >= g.L) return;   // unused entry or the rows that keep the base output
+                const int kbeg = range * g.prep_kper;
+                shrink_rows<256, 1, false>(g.x, (const bf16_t *)A.p[grp], g.ranks.r[grp], rows, g.H, g.r,
+                                           (uint32_t)((size_t)g.T * g.H * 2), g.T, kbeg, min(g.H, kbeg + g.prep_kper), range,
+                                           g.prep_ranges, nullptr, g.S_out, stage0, stage1, stage2, stage3,
+                                           (float (*)[1][32][33])stage4, scr + GROUP_SMALL_SCRATCH);
+            }
+            return;
+        }
+    }
     int mt, nt;
     {
         const int total = g.mtiles * g.ntiles, chunk = (total + 7) >> 3;
-        const int l = ((int)blockIdx.x & 7) * chunk + ((int)blockIdx.x >> 3);
+        const int l = (bx & 7) * chunk + (bx >> 3);
         if (l >= total) return;  // grid is padded to a multiple of 8; uniform across the workgroup
         const int panel = l / (4 * g.ntiles), rem = l - panel * 4 * g.ntiles;
         const int pm = min(4, g.mtiles - 4 * panel);
@@ -211,7 +250,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     for (int jj = 0; jj < NCW; ++jj) vwb[jj] = w_col_ok(jj, lane) ? (uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
     const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
     // base K-slices of this workgroup: all of them, or the range of its split
-    const int kt0 = SPLIT ? (int)blockIdx.y * g.kps : 0;
+    const int kt0 = SPLIT ? by * g.kps : 0;
     const int KT = SPLIT ? min(g.H / BK, kt0 + g.kps) : g.H / BK;
     const int n_base = KT - kt0;
 
@@ -408,7 +447,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 4;
-        float *out = g.partial + (size_t)blockIdx.y * g.T * g.N;
+        float *out = g.partial + (size_t)by * g.T * g.N;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
 #pragma unroll
@@ -512,6 +551,10 @@ GemmPlan plan_gemm(int T, int H, int N)
         // hidden dimension into splits (each split costs an extra pass over its fp32 partials)
         int max_splits = 1;
         if (tiles * 2 <= CUS) max_splits = (int)std::min<long>(std::min(8, KT), CUS / tiles);
+        // A batch of one token tile leaves a quarter of the compute units to the workgroups that group and
+        // shrink it inside the projection kernel (see prep_in_projection): measured 40 us per step against
+        // 48 us when the projection takes 240 of the 256 units (decode batch of 256 rows, 8B shapes).
+        if (mtiles == 1 && max_splits > 1) max_splits = (int)std::max<long>(1, std::min<long>(max_splits, (CUS - CUS / 4) / tiles));
         for (int sp = 1; sp <= max_splits; ++sp) {
             if (g_force_splits && sp != std::min(g_force_splits, std::min(8, KT))) continue;
             const int kps = (KT + sp - 1) / sp;
@@ -535,17 +578,25 @@ size_t gemm_partial_bytes(int T, int H, int N)
 }
 
 template <int NTW>
-static void launch_ntw(const GemmArgs &g, const PtrTable &B, int splits, hipStream_t stream)
+static void launch_ntw(const GemmArgs &g, const PtrTable &B, const PtrTable &A, hipStream_t stream)
 {
     const dim3 block(GEMM_THREADS);
-    const int tiles8 = (g.mtiles * g.ntiles + 7) / 8 * 8;  // see the tile order in the kernel
-    if (splits > 1)
-        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, true>), dim3(tiles8, splits), block, 0, stream, g, B);
+    if (g.splits > 1)
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, true>), dim3(g.tiles8 * g.splits + g.prep_wgs), block, 0, stream, g, B, A);
     else
-        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, false>), dim3(tiles8), block, 0, stream, g, B);
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, false>), dim3(g.tiles8), block, 0, stream, g, B, A);
 }
 
-int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projection)
+// Decode-sized bf16 batches: classification, grouping and shrink run inside the split projection kernel,
+// on workgroups behind its own (the projection of such a batch does not fill every compute unit).
+bool prep_in_projection(const Fwd &f)
+{
+    if (f.dtype != ALORA_BF16 || f.L <= 0 || f.T <= 0 || f.T > GROUP_SMALL_ROWS || f.r > 32) return false;
+    const GemmPlan plan = plan_gemm(f.T, f.H, f.N);
+    return plan.splits > 1 && plan.ntw == 2;
+}
+
+int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEvent_t after_projection)
 {
     if (f.T == 0) return 0;
     const GemmPlan plan = plan_gemm(f.T, f.H, f.N);
@@ -561,13 +612,23 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projectio
     g.partial = f.partial;
     g.bias = (const bf16_t *)f.bias;
     g.ranks = f.ranks;
-    if (plan.ntw == 4) launch_ntw<4>(g, B, plan.splits, f.stream);
-    else if (plan.ntw == 3) launch_ntw<3>(g, B, plan.splits, f.stream);
-    else launch_ntw<2>(g, B, plan.splits, f.stream);
+    g.tiles8 = (g.mtiles * g.ntiles + 7) / 8 * 8;   // see the tile order in the kernel
+    g.splits = plan.splits;
+    const bool prep = prep_in_projection(f);
+    // shrink ranges of the prep workgroups: about 1024 wide, at most 4, none empty
+    const int want = std::max(1, std::min(4, f.H / 1024));
+    g.prep_kper = ((f.H / 64 + want - 1) / want) * 64;
+    g.prep_ranges = (f.H + g.prep_kper - 1) / g.prep_kper;
+    g.prep_wgs = prep ? f.n_blocks * g.prep_ranges : 0;
+    g.prep = GroupSmallArgs{f.aid, f.seg, f.pos, f.start, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks};
+    g.S_out = f.S;
+    if (plan.ntw == 4) launch_ntw<4>(g, B, A, f.stream);
+    else if (plan.ntw == 3) launch_ntw<3>(g, B, A, f.stream);
+    else launch_ntw<2>(g, B, A, f.stream);
     int e = (int)hipGetLastError();
     if (!e && after_projection) e = (int)hipEventRecord(after_projection, f.stream);
     if (e || plan.splits == 1) return e;
-    return launch_finish_bf16(f, B, plan.splits);
+    return launch_finish_bf16(f, B, plan.splits, prep ? g.prep_ranges : plan_shrink(f.T, f.H, f.N, f.L, f.r).splits);
 }
 
 }  // namespace alora

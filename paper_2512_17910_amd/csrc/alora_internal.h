@@ -82,8 +82,9 @@ int launch_classify_group(const Fwd &f);
 int launch_shrink_f32(const Fwd &f, const PtrTable &A);
 int launch_gemm_f32(const Fwd &f, const PtrTable &B);
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A);
-int launch_gemm_bf16(const Fwd &f, const PtrTable &B, hipEvent_t after_projection);
-int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits);
+int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEvent_t after_projection);
+bool prep_in_projection(const Fwd &f);   // grouping and shrink run inside the split projection kernel
+int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits);
 struct GemmPlan {
     int ntw;     // 32-wide feature tiles per wavefront (tile width 64 * ntw)
     int splits;  // 1: fused kernel; > 1: split hidden dimension + finishing kernel
