@@ -332,3 +332,49 @@ def test_wide_hidden_high_rank_shrink_cuts_blocks_into_ranges_and_combines_them_
             db.reset()
             db.forward()
             assert all(np.array_equal(a, b) for a, b in zip(first, (raw_bits(db.q), raw_bits(db.kc), raw_bits(db.vc))))
+
+
+def _decode_batch(n_rows, n_adapters, rank, kind, seed, hidden=256):
+    """n_rows one-token sequences: 'mixed' = base rows, never-activated and activated rows of random
+    adapters; 'one' = every row adapted by the last adapter; 'base' = no row adapted."""
+    rng = np.random.default_rng(seed)
+    segs = []
+    for s in range(n_rows):
+        p = int(rng.integers(1, 60))
+        if kind == "base":
+            a, st = -1, 0
+        elif kind == "one":
+            a, st = n_adapters - 1, 0
+        else:
+            a = -1 if rng.random() < 0.2 else int(rng.integers(0, n_adapters))
+            st = int(rng.integers(0, p + 2))          # p + 1: not activated yet
+        segs.append(wl.Segment(s, p, 1, a, st))
+    return wl.assemble(f"decode-{kind}-{n_rows}x{n_adapters}r{rank}", "bf16", hidden, 4, 2, 64, n_adapters, rank, 16, segs,
+                       [64] * n_rows, seed=500 + seed, extra_blocks=2)
+
+
+@pytest.mark.parametrize("forced", [(0, 0), (2, 2), (2, 4)], ids=["auto", "128-wide-2-splits", "128-wide-4-splits"])
+@pytest.mark.parametrize("n_rows", [1, 31, 32, 33, 64, 255, 256, 257])
+def test_batches_of_at_most_256_rows_are_grouped_and_shrunk_inside_the_projection_kernel(tuning, n_rows, forced):
+    """Up to 256 rows the split projection kernel classifies, groups and shrinks the batch on workgroups of
+    its own (257 rows take the separate kernels): integer results bit-exact against the oracle's stable
+    grouping, outputs within tolerance, for many small groups (128 adapters), one full group, no group.
+    The forced tilings are the ones that path needs (128-wide tiles, hidden dimension split)."""
+    tuning(*forced)
+    _check_full(_decode_batch(n_rows, 128, 8, "mixed", n_rows))
+    _check_full(_decode_batch(n_rows, 5, 32, "mixed", 1000 + n_rows, hidden=1024))
+    _check_full(_decode_batch(n_rows, 3, 16, "one", 2000 + n_rows))
+    _check_full(_decode_batch(n_rows, 3, 16, "base", 3000 + n_rows))
+
+
+def test_in_kernel_grouping_with_bias_and_per_adapter_ranks(tuning):
+    tuning(2, 4)
+    w = wl.with_variants(_decode_batch(200, 4, 32, "mixed", 77, hidden=2048), ranks=(8, 32, 16, 24), bias=True)
+    db = DeviceBatch(w)
+    db.forward()
+    x, W, A, B = host_operands(w)
+    ref_active, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+    y = oracle.alora_rows_var(x, W, A, B, w.token_adapter_ids, act, np.arange(w.T, dtype=np.int32), wl.widen_f64(w.bias, w.dtype))
+    assert maxnorm_rel(to_f64(db.q), y[:, : w.Nq]) <= TOL["bf16"]
+    wr = w.slot_mapping[w.slot_mapping >= 0]
+    assert maxnorm_rel(to_f64(db.kc)[wr], y[w.slot_mapping >= 0][:, w.Nq: w.Nq + w.Nkv]) <= TOL["bf16"]
