@@ -145,12 +145,22 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
  *                  shape [adapter_ranks[i], N], 1 <= adapter_ranks[i] <= dims->rank (bf16: multiples
  *                  of 8), else ALORA_ESHAPE.  NULL = every adapter has rank dims->rank.  Read during
  *                  the call only.
+ *   reuse_grouping App. B builds the activation mask once per forward pass of the model and every
+ *                  layer reads it.  Nonzero: skip classification and grouping and use the results a
+ *                  previous call (alora_qkv_classify_group, alora_qkv_forward[_ex], a graph launch)
+ *                  left in THIS workspace for the same dims, token_adapter_ids, token_seg_ids,
+ *                  token_positions and activation_start -- the per-layer call of a model whose
+ *                  layers share one token batch.  The calls must be stream-ordered.  A workspace
+ *                  that holds no such results gives wrong outputs (indices read from it are range-
+ *                  checked, so nothing outside the buffers is touched).  Decode-sized bf16 batches
+ *                  regroup inside the projection kernel anyway; the flag changes nothing there.
  * Per-module factors (separate A^Q, A^K, A^V with B^Q, B^K, B^V; Sec. 2.3) are the block-structured
  * special case: A = [A^Q | A^K | A^V] of rank 3r and B with B^Q, B^K, B^V on its block diagonal.
  */
 typedef struct alora_extras {
     const void *bias;
     const int32_t *adapter_ranks;
+    int32_t reuse_grouping;
 } alora_extras;
 int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
                          const void *W_qkv, const void *const *A, const void *const *B,

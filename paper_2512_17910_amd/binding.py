@@ -33,7 +33,7 @@ class AloraWsLayout(ctypes.Structure):
 
 
 class AloraExtras(ctypes.Structure):
-    _fields_ = [("bias", ctypes.c_void_p), ("adapter_ranks", ctypes.c_void_p)]
+    _fields_ = [("bias", ctypes.c_void_p), ("adapter_ranks", ctypes.c_void_p), ("reuse_grouping", ctypes.c_int32)]
 
 
 class AloraAttnDims(ctypes.Structure):
@@ -187,9 +187,11 @@ def alora_qkv_forward(x, token_adapter_ids, activation_start, W_qkv, A: Sequence
 
 def alora_qkv_forward_ex(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
                          q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims,
-                         workspace, bias=None, adapter_ranks=None, stream=None) -> None:
-    """alora_qkv_forward with a layer bias [N] (device tensor) and/or one rank per adapter (host ints)."""
-    ex = AloraExtras(_ptr(bias), None)
+                         workspace, bias=None, adapter_ranks=None, stream=None, reuse_grouping: bool = False) -> None:
+    """alora_qkv_forward with a layer bias [N] (device tensor) and/or one rank per adapter (host ints);
+    reuse_grouping: use the classification/grouping an earlier call left in this workspace for the same
+    token batch (the per-layer call of a model whose layers share one batch)."""
+    ex = AloraExtras(_ptr(bias), None, 1 if reuse_grouping else 0)
     keep = None
     if adapter_ranks is not None:
         keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])
@@ -210,7 +212,7 @@ def alora_qkv_graph_create(x, token_adapter_ids, activation_start, W_qkv, A: Seq
     alora_qkv_graph_launch / alora_qkv_graph_destroy.  The caller keeps every tensor alive and rewrites
     their contents in place between launches."""
     h = ctypes.c_void_p(None)
-    ex = AloraExtras(_ptr(bias), None)
+    ex = AloraExtras(_ptr(bias), None, 0)
     keep = None
     if adapter_ranks is not None:
         keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])

@@ -64,7 +64,7 @@ static Layout make_layout(const alora_dims *d)
     l.blocktab = o; o += up256(16 * (size_t)l.n_blocks);
     l.n_items = d->dtype == ALORA_BF16 ? shrink_items(d->T, d->n_adapters) : 0;
     l.items = o;    o += up256(16 * (size_t)l.n_items);
-    l.counters = o; o += up256(4 * (size_t)(l.n_items ? l.n_blocks : 0));
+    l.counters = o; o += up256(4 * (size_t)l.n_items);   // one per block; indexed below n_items
     l.hist = o;     o += up256(group_hist_bytes(d->T));
     l.partial = o;
     if (d->dtype == ALORA_BF16) o += up256(gemm_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
@@ -203,6 +203,7 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
     RankTable ranks;
     for (int i = 0; i < ALORA_MAX_ADAPTERS; ++i) ranks.r[i] = (uint8_t)dims->rank;
     const void *bias = nullptr;
+    const bool reuse_grouping = extras && extras->reuse_grouping != 0;
     if (extras) {
         bias = extras->bias;
         if (bias && misaligned16(bias)) return ALORA_EINVAL;
@@ -232,7 +233,7 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
     if (timed) timed = (g_prof.seen++ % g_prof.every) == 0;
     // decode-sized bf16 batches: grouping and shrink ride in the projection kernel (two launches in all)
     const bool prep_inside = prep_in_projection(f);
-    int e = prep_inside ? 0 : launch_classify_group(f);
+    int e = (prep_inside || reuse_grouping) ? 0 : launch_classify_group(f);
     if (!e) {
         if (f.dtype == ALORA_F32) {
             e = launch_shrink_f32(f, ta);

@@ -13,14 +13,16 @@ namespace alora {
 __global__ __launch_bounds__(256) void shrink_f32_kernel(const float *__restrict__ x, PtrTable A, RankTable ranks,
                                                          const int32_t *__restrict__ aid,
                                                          const int32_t *__restrict__ perm,
-                                                         const int32_t *__restrict__ offsets, int L, int H, int r,
+                                                         const int32_t *__restrict__ offsets, int T, int L, int H, int r,
                                                          float *__restrict__ S)
 {
     __shared__ float red[4][64];
     const int n_act = offsets[L];
     if ((int)blockIdx.x >= n_act) return;
     const int t = perm[blockIdx.x];
+    if (t < 0 || t >= T) return;   // (perm may be what an earlier call left in the workspace: range-checked)
     const int a = aid[t];
+    if (a < 0 || a >= L) return;
     const float *xr = x + (size_t)t * H;
     const float *Aa = (const float *)A.p[a];
     const int ra = ranks.r[a];   // this adapter's rank: A_a is [H, ra]; S keeps the common row pitch r
@@ -113,7 +115,7 @@ int launch_shrink_f32(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;
     hipLaunchKernelGGL(shrink_f32_kernel, dim3(f.T), dim3(256), 0, f.stream, (const float *)f.x, A, f.ranks, f.aid,
-                       f.perm, f.offsets, f.L, f.H, f.r, (float *)f.S);
+                       f.perm, f.offsets, f.T, f.L, f.H, f.r, (float *)f.S);
     return (int)hipGetLastError();
 }
 

@@ -40,14 +40,16 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
     const int4 entry = blocktab[blockIdx.x];
     const int a = entry.x, j0 = entry.y, cnt = entry.z;
     if (a < 0) return;  // unused table entry; uniform across the workgroup
+    if (a > L || j0 < 0 || cnt < 0 || cnt > 32 || j0 + cnt > T) return;   // not a table of this batch
     const int N = Nq + 2 * Nkv;
     const int n0 = blockIdx.y * FIN_COLS;
     const int tid = threadIdx.x;
     const bool adapted = a < L;
     const int ra = adapted ? ranks.r[a] : 0;   // this group's rank; S and B_a rows beyond it do not exist
     const int i = tid >> 5, c = tid & 31, n = n0 + 8 * c;
-    const bool live = i < cnt && n < N;
-    const int t = i < cnt ? perm[j0 + i] : -1;
+    int t = i < cnt ? perm[j0 + i] : -1;
+    if (t >= T) t = -1;
+    const bool live = t >= 0 && n < N;
 
     // everything that depends on the row id, issued together
     f32x4 plo[SPLITS], phi[SPLITS];

@@ -302,6 +302,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     int epa = 0;             // expand slices per adapter
     if (!SPLIT) {
         asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a_row), "+v"(slot_row) : "n"(NC * (NST - 1)) : "memory");
+        if (a_row >= g.L) a_row = -1;   // (a workspace that holds no grouping of this batch: stay inside the tables)
         slot_lds[tid] = slot_row;
         arow[tid] = a_row;
         if (tid < ALORA_MAX_ADAPTERS) present[tid] = 0;

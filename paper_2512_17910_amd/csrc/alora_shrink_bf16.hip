@@ -58,10 +58,17 @@ __global__ __launch_bounds__(256) void shrink_bf16_kernel(const bf16_t *__restri
     const int range = WORK_LIST ? (entry.w & 15) : (int)blockIdx.y;
     const int n_ranges = WORK_LIST ? ((entry.w >> 4) & 15) : (int)gridDim.y;
     if (WORK_LIST) kper = (entry.z >> 8) * 64;
+    if (kper <= 0 || kper > H + 63 || range < 0 || range >= n_ranges || n_ranges > ALORA_SHRINK_MAX_SPLITS) return;
     const int kbeg = range * kper, kend = min(H, kbeg + kper);
 
     const int tid = threadIdx.x;
-    if (tid < SHRINK_ROWS) rows_t[tid] = tid < cnt ? perm[j0 + tid] : -1;
+    // (the table and perm may be what an earlier call left in the workspace: indices are range-checked)
+    if (j0 < 0 || cnt < 0 || cnt > SHRINK_ROWS || j0 + cnt > T || n_ranges < 1 || kbeg >= H) return;
+    if (WORK_LIST && (uint32_t)(entry.w >> 8) >= gridDim.x) return;
+    if (tid < SHRINK_ROWS) {
+        const int t = tid < cnt ? perm[j0 + tid] : -1;
+        rows_t[tid] = (t >= 0 && t < T) ? t : -1;
+    }
     __syncthreads();
     // this adapter's rank (multiple of 8): A_a is [H, rk]; S keeps the common pitch r
     shrink_rows<KSL, NT, WORK_LIST>(x, (const bf16_t *)A.p[a], ranks.r[a], rows_t, H, r, x_bytes, T, kbeg, kend, range, n_ranges,

@@ -208,6 +208,8 @@ __device__ __forceinline__ void shrink_rows(const bf16_t *__restrict__ x, const 
         *is_last = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n_ranges - 1;
     __syncthreads();
     if (!*is_last) return;
+    // the counter is ready for the next call on this workspace (one that reuses the grouping results)
+    if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     constexpr int PER = 32 * 32 * NT / 256;
     // all loads first (they are round trips past the L2), then the sums in range order
     float part[PER][ALORA_SHRINK_MAX_SPLITS], sum[PER];

@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2512_17910_amd import binding as ab
 from paper_2512_17910_amd import workloads as wl
-from gpu_util import DeviceBatch, TOL, check_grouping, host_operands, maxnorm_rel, raw_bits, to_f64
+from gpu_util import DeviceBatch, TOL, check_grouping, host_operands, maxnorm_rel, raw_bits, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -378,3 +378,42 @@ def test_in_kernel_grouping_with_bias_and_per_adapter_ranks(tuning):
     assert maxnorm_rel(to_f64(db.q), y[:, : w.Nq]) <= TOL["bf16"]
     wr = w.slot_mapping[w.slot_mapping >= 0]
     assert maxnorm_rel(to_f64(db.kc)[wr], y[w.slot_mapping >= 0][:, w.Nq: w.Nq + w.Nkv]) <= TOL["bf16"]
+
+
+def _as_next_layer(w, seed):
+    """The same token batch entering another layer: same metadata, new x, W, A, B (and bias)."""
+    v = wl.assemble(w.name + "-next", w.dtype, w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_adapters, w.rank,
+                    w.block_size, w.segments, [s.first_pos + s.n_tokens for s in w.segments], seed=seed, extra_blocks=5)
+    for name in ("token_adapter_ids", "token_seg_ids", "token_positions", "activation_start", "slot_mapping"):
+        setattr(v, name, getattr(w, name))
+    v.n_slots = w.n_slots
+    return v
+
+
+@pytest.mark.parametrize("kw", [dict(dtype="bf16", seed=2, seq_lens=(300, 41, 1, 77, 256, 3), pad_every=17),
+                                dict(dtype="bf16", seed=21, hidden=8192, rank=64, n_adapters=3, seq_lens=(300, 41, 1, 77, 130)),
+                                dict(dtype="f32", seed=7, rank=64, pad_every=5),
+                                dict(dtype="bf16", seed=9, seq_lens=(100, 60))],
+                         ids=["bf16-prefill", "bf16-wide-ranged-shrink", "f32", "bf16-decode-sized"])
+def test_a_later_layer_reuses_the_grouping_left_in_the_workspace(kw):
+    """App. B builds the mask once per forward pass.  Layer 1 runs the whole call; layers 2 and 3 (same token
+    batch, other activations and weights) run with reuse_grouping on the same workspace and must give
+    exactly the bits of a complete call on those inputs."""
+    w1 = wl.small_mixed(**kw)
+    db = DeviceBatch(w1)
+    db.forward()
+    for layer in (2, 3):
+        wn = _as_next_layer(w1, 7000 + layer)
+        assert np.array_equal(wn.slot_mapping, w1.slot_mapping)
+        fresh = DeviceBatch(wn)
+        fresh.forward()
+        x, W = to_dev(wn.x, wn.dtype), to_dev(wn.W, wn.dtype)
+        A, B = [to_dev(a, wn.dtype) for a in wn.A], [to_dev(b, wn.dtype) for b in wn.B]
+        db.reset()
+        ab.alora_qkv_forward_ex(x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot, wn.block_size, db.dims, db.ws,
+                                reuse_grouping=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(raw_bits(db.q), raw_bits(fresh.q))
+        assert np.array_equal(raw_bits(db.kc), raw_bits(fresh.kc)) and np.array_equal(raw_bits(db.vc), raw_bits(fresh.vc))
+        ref = _oracle_full(wn)
+        assert maxnorm_rel(to_f64(db.q), ref.q_out) <= TOL[wn.dtype]
