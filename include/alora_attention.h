@@ -26,7 +26,7 @@
  * once.  out may not alias q.
  *
  * Limits: head_dim in {64, 128}; n_q_heads / n_kv_heads in {1, 2, 4, 8}; block_size >= 1;
- * n_tokens * n_kv_heads <= 2^31 - 1.  One workgroup per (row, K/V head): meant for decode-sized
+ * n_tokens * n_kv_heads <= 2^31 - 1; n_slots <= 2^31 - 1.  One workgroup per (row, K/V head): meant for decode-sized
  * batches and short suffixes (rows of one sequence each read the context again).
  *
  * Errors: ALORA_EINVAL (null pointer, negative size, unknown dtype, misaligned pointer),

@@ -86,7 +86,7 @@ def main() -> None:
            "config": {"workload": name, "rows": n_seq, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "block_size": bs,
                       "context_positions": int(lens.sum()), "max_context": int(lens.max())},
            "roofline": {"bound": "hbm", "achieved": io_bytes / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
-                        "frac": io_bytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None, "kernel": "paged_attention_kernel<128, 4, true>",
+                        "frac": io_bytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None, "kernel": "paged_attention_kernel<128, 4, true, true>",
                         "kernel_ms": ms, "algorithmic_bytes_per_launch": io_bytes}}
 
     print(json.dumps(res))

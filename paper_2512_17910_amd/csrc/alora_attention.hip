@@ -100,7 +100,12 @@ __device__ __forceinline__ float dot8(const Raw8<false> &q, const Raw8<false> &k
     return d;
 }
 
-template <int D, int G, bool BF16>
+// The running maximum starts at a large negative FINITE number: differences with it stay finite, so the
+// softmax needs no "nothing seen yet" cases (a position that is left out scores -inf and weighs
+// exp2(-inf) = 0).  Scores below it are treated like -inf.
+constexpr float M_FLOOR = -1.0e30f;
+
+template <int D, int G, bool BF16, bool POW2>
 __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
 {
     constexpr int LPP = D / 8;         // lanes per context position
@@ -122,8 +127,9 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     if (sq >= 0 && sq < a.n_seqs && p >= 0) n_ctx = (int)(p + 1ll < cap ? p + 1ll : cap);
     const int32_t *bt = a.bt + (size_t)(n_ctx ? sq : 0) * a.max_blocks;
     const int Nkv = a.Hkv * D;
-    const size_t col = (size_t)hk * D + 8 * c;
+    const int col = hk * D + 8 * c;
     const int jl = wave * PPW + grp;   // this lane group's position inside a step
+    const long long n_blocks = a.n_slots / a.bs;
 
     Raw8<BF16> qr[G];
 #pragma unroll
@@ -132,47 +138,74 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     float m[G], l[G], acc[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        m[g] = NEG_INF;
+        m[g] = M_FLOOR;
         l[g] = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
     }
 
-    // block-table entries of the block starting at j0 (-1 past the context)
+    // block-table entries of the block starting at j0 (-1 past the context).  Only the loads are issued
+    // here: the entries are first looked at one block later, in fetch, so their latency is covered.
     auto lookup = [&](int j0, int (&blk)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + u * PPI + jl;
             blk[u] = -1;
-            if (j < n_ctx) blk[u] = bt[a.bs_shift >= 0 ? (j >> a.bs_shift) : (j / a.bs)];
+            if (j < n_ctx) blk[u] = bt[POW2 ? (j >> a.bs_shift) : (j / a.bs)];
         }
     };
-    // K and V chunks of the block starting at j0, through table entries looked up earlier
-    auto fetch = [&](int j0, const int (&blk)[U], Raw8<BF16> (&kr)[U], Raw8<BF16> (&vr)[U], bool (&ok)[U]) {
+    // K and V chunks of the block starting at j0, through table entries looked up earlier; a position past
+    // the context or with a table entry outside the cache is left out (zero chunks, validity bit clear).
+    // Returns the validity of this lane's positions, one bit per step.
+    auto fetch = [&](int j0, const int (&blk)[U], Raw8<BF16> (&kr)[U], Raw8<BF16> (&vr)[U]) {
+        unsigned ok = 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + u * PPI + jl;
-            const int bi = a.bs_shift >= 0 ? (j >> a.bs_shift) : (j / a.bs);
-            const long long slot = (long long)blk[u] * a.bs + (j - bi * a.bs);
+            const bool have = blk[u] >= 0 && blk[u] < n_blocks;   // blk is -1 past the context
+            ok |= (unsigned)have << u;
             kr[u].zero();
             vr[u].zero();
-            ok[u] = blk[u] >= 0 && slot < a.n_slots;   // blk is -1 past the context
-            if (ok[u]) {
-                kr[u].load(a.kc, (size_t)slot * Nkv + col);
-                vr[u].load(a.vc, (size_t)slot * Nkv + col);
+            if (have) {
+                const int off = POW2 ? (j & (a.bs - 1)) : (j % a.bs);
+                const size_t at = ((size_t)blk[u] * a.bs + off) * Nkv + col;
+                kr[u].load(a.kc, at);
+                vr[u].load(a.vc, at);
             }
         }
+        return ok;
     };
     // scores, running softmax (rescaled once per block) and weighted sum of V for one block
-    auto consume = [&](const Raw8<BF16> (&kr)[U], const Raw8<BF16> (&vr)[U], const bool (&ok)[U]) {
+    auto consume = [&](const Raw8<BF16> (&kr)[U], const Raw8<BF16> (&vr)[U], unsigned ok) {
         float s[U][G];   // in units of log2
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float d = group_sum<LPP>(dot8(qr[g], kr[u]));
-                s[u][g] = ok[u] ? d * a.scale_log2e : NEG_INF;
-            }
+            for (int g = 0; g < G; ++g) s[u][g] = dot8(qr[g], kr[u]);
+        // the sums over the lanes of a position, one reduction step at a time over all scores: consecutive
+        // DPP instructions then work on different registers
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[u][g] = dpp_add<0xB1>(s[u][g]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[u][g] = dpp_add<0x4E>(s[u][g]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[u][g] = dpp_add<0x141>(s[u][g]);
+        if (LPP == 16) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[u][g] = dpp_add<0x140>(s[u][g]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[u][g] = ((ok >> u) & 1u) ? s[u][g] * a.scale_log2e : NEG_INF;
         float pw[U][G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -180,16 +213,15 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
 #pragma unroll
             for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][g]);
             const float mn = fmaxf(m[g], mx);
-            const bool none = mn == NEG_INF;     // nothing seen yet by this lane group
-            const float corr = none ? 1.f : __builtin_amdgcn_exp2f(m[g] - mn);
+            const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
+            m[g] = mn;
             float ls = l[g] * corr;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                pw[u][g] = none ? 0.f : __builtin_amdgcn_exp2f(s[u][g] - mn);
+                pw[u][g] = __builtin_amdgcn_exp2f(s[u][g] - mn);
                 ls += pw[u][g];
             }
             l[g] = ls;
-            m[g] = mn;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
         }
@@ -204,20 +236,19 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
         }
     };
 
-    // Two register sets: while one block is consumed the next block's K/V loads and the table entries
-    // of the block after it are in flight.
+    // Two register sets: while one block is consumed the next block's K/V loads and the table entries of
+    // the block after it are in flight.
     int blkA[U], blkB[U];
     Raw8<BF16> krA[U], vrA[U], krB[U], vrB[U];
-    bool okA[U], okB[U];
     lookup(0, blkA);
-    fetch(0, blkA, krA, vrA, okA);
+    unsigned okA = fetch(0, blkA, krA, vrA), okB;
     lookup(BLK, blkB);
     for (int j0 = 0; j0 < n_ctx; j0 += 2 * BLK) {
-        fetch(j0 + BLK, blkB, krB, vrB, okB);
+        okB = fetch(j0 + BLK, blkB, krB, vrB);
         lookup(j0 + 2 * BLK, blkA);
         consume(krA, vrA, okA);
         if (j0 + BLK < n_ctx) {
-            fetch(j0 + 2 * BLK, blkA, krA, vrA, okA);
+            okA = fetch(j0 + 2 * BLK, blkA, krA, vrA);
             lookup(j0 + 3 * BLK, blkB);
             consume(krB, vrB, okB);
         }
@@ -230,9 +261,7 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
         for (int g = 0; g < G; ++g) {
             const float mo = __shfl_xor(m[g], off), lo = __shfl_xor(l[g], off);
             const float mn = fmaxf(m[g], mo);
-            const bool none = mn == NEG_INF;
-            const float ca = none ? 1.f : __builtin_amdgcn_exp2f(m[g] - mn);
-            const float cb = none ? 0.f : __builtin_amdgcn_exp2f(mo - mn);
+            const float ca = __builtin_amdgcn_exp2f(m[g] - mn), cb = __builtin_amdgcn_exp2f(mo - mn);
             l[g] = l[g] * ca + lo * cb;
             m[g] = mn;
 #pragma unroll
@@ -259,13 +288,11 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
 #pragma unroll
         for (int w = 1; w < 4; ++w) M = fmaxf(M, sm[w][g]);
         float L = 0.f, o = 0.f;
-        if (M != NEG_INF) {
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float f = __builtin_amdgcn_exp2f(sm[w][g] - M);
-                L += sl[w][g] * f;
-                o += sacc[w][g][dd] * f;
-            }
+        for (int w = 0; w < 4; ++w) {
+            const float f = __builtin_amdgcn_exp2f(sm[w][g] - M);
+            L += sl[w][g] * f;
+            o += sacc[w][g][dd] * f;
         }
         const float y = L > 0.f ? o / L : 0.f;
         const size_t at = ((size_t)t * a.Hq + (size_t)hk * G + g) * D + dd;
@@ -278,8 +305,11 @@ template <int D, int G>
 static void launch_dg(const AttnArgs &a, bool bf16, hipStream_t st)
 {
     const dim3 grid((unsigned)a.T * (unsigned)a.Hkv);
-    if (bf16) hipLaunchKernelGGL((paged_attention_kernel<D, G, true>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((paged_attention_kernel<D, G, false>), grid, dim3(256), 0, st, a);
+    const bool pow2 = a.bs_shift >= 0;
+    if (bf16 && pow2) hipLaunchKernelGGL((paged_attention_kernel<D, G, true, true>), grid, dim3(256), 0, st, a);
+    else if (bf16) hipLaunchKernelGGL((paged_attention_kernel<D, G, true, false>), grid, dim3(256), 0, st, a);
+    else if (pow2) hipLaunchKernelGGL((paged_attention_kernel<D, G, false, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((paged_attention_kernel<D, G, false, false>), grid, dim3(256), 0, st, a);
 }
 
 template <int D>
@@ -305,7 +335,7 @@ static int check_dims(const alora_attn_dims *d)
     if (d->n_q_heads % d->n_kv_heads) return ALORA_ESHAPE;
     const int G = d->n_q_heads / d->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return ALORA_ESHAPE;
-    if ((long long)d->n_tokens * d->n_kv_heads > 0x7fffffffll) return ALORA_ESHAPE;
+    if ((long long)d->n_tokens * d->n_kv_heads > 0x7fffffffll || d->n_slots > 0x7fffffffll) return ALORA_ESHAPE;
     return ALORA_OK;
 }
 
