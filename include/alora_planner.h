@@ -29,7 +29,9 @@
  *
  * Thread safety: one planner object must not be used from two threads at once.
  * Statuses are those of alora_qkv.h plus ALORA_ENOBLOCKS; on any error the planner is unchanged
- * and no output array element has been written.
+ * and no output array element has been written (one exception: alora_planner_commit that runs out
+ * of host memory, ALORA_ENOMEM, may have registered part of the request's blocks; the call can be
+ * repeated).
  */
 #ifndef ALORA_PLANNER_H
 #define ALORA_PLANNER_H

@@ -68,6 +68,7 @@ extern "C" {
 #define ALORA_EWORKSPACE (-3)  /* workspace null, misaligned (256 B) or too small          */
 #define ALORA_EHIP (-4)        /* a HIP call failed; see alora_last_hip_error()            */
 #define ALORA_EDATA (-5)       /* alora_qkv_validate found a violated data precondition    */
+#define ALORA_ENOMEM (-6)      /* a host-side allocation failed (validate calls, planner)   */
 
 /* Sizes of one call plus the two per-token index arrays of App. B. */
 typedef struct alora_dims {

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("ALORA_QKV_LIB") or os.path.join(HERE, "libalora_qkv.so")
 
 ALORA_F32, ALORA_BF16 = 0, 1
-ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_EWORKSPACE, ALORA_EHIP, ALORA_EDATA = 0, -1, -2, -3, -4, -5
+ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_EWORKSPACE, ALORA_EHIP, ALORA_EDATA, ALORA_ENOMEM = 0, -1, -2, -3, -4, -5, -6
 ALORA_MAX_ADAPTERS, ALORA_MAX_RANK = 128, 64
 
 

@@ -1,5 +1,6 @@
 // C ABI of libalora_qkv: argument checking, workspace carving and the launch sequence.
 // Host code only; every step of the path runs in the kernels of the other translation units.
+#include <new>
 #include <vector>
 #include <algorithm>
 #include "alora_internal.h"
@@ -124,6 +125,7 @@ const char *alora_status_string(int s)
     case ALORA_EWORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case ALORA_EHIP: return "a HIP call failed (see alora_last_hip_error)";
     case ALORA_EDATA: return "device data violates a documented precondition";
+    case ALORA_ENOMEM: return "a host-side allocation failed";
     case -7: return "not enough free cache blocks (planner)";
     default: return "unknown status";
     }
@@ -344,9 +346,14 @@ int alora_qkv_profile_begin_every(int max_calls, int every)
 {
     if (max_calls <= 0 || max_calls > (1 << 20) || every < 1) return ALORA_EINVAL;
     if (g_prof.on) return ALORA_EINVAL;
-    g_prof.ev0.assign((size_t)max_calls, nullptr);
-    g_prof.ev1.assign((size_t)max_calls, nullptr);
-    for (int i = 0; i < max_calls; ++i) {
+    const int pairs = (max_calls + every - 1) / every;   // calls that can be measured
+    try {
+        g_prof.ev0.assign((size_t)pairs, nullptr);
+        g_prof.ev1.assign((size_t)pairs, nullptr);
+    } catch (const std::bad_alloc &) {
+        return ALORA_ENOMEM;
+    }
+    for (int i = 0; i < pairs; ++i) {
         hipError_t e = hipEventCreate(&g_prof.ev0[i]);
         if (!e) e = hipEventCreate(&g_prof.ev1[i]);
         if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
@@ -394,6 +401,7 @@ int alora_qkv_validate(const int32_t *token_adapter_ids, const int32_t *activati
     if (T == 0) return ALORA_OK;
     if (!token_adapter_ids || !slot_mapping || !dims->token_seg_ids || !dims->token_positions) return ALORA_EINVAL;
     if (dims->n_segments > 0 && !activation_start) return ALORA_EINVAL;
+    try {
     std::vector<int32_t> aid(T), seg(T), pos(T), start((size_t)dims->n_segments);
     std::vector<int64_t> slot(T);
     hipError_t e = hipMemcpy(aid.data(), token_adapter_ids, 4 * T, hipMemcpyDeviceToHost);
@@ -415,6 +423,9 @@ int alora_qkv_validate(const int32_t *token_adapter_ids, const int32_t *activati
     std::sort(used.begin(), used.end());
     if (std::adjacent_find(used.begin(), used.end()) != used.end()) return ALORA_EDATA;
     return ALORA_OK;
+    } catch (const std::bad_alloc &) {
+        return ALORA_ENOMEM;
+    }
 }
 
 }  // extern "C"

@@ -16,6 +16,7 @@
 // (lane groups by shuffles, wavefronts through LDS), so the result does not depend on timing.
 #include "alora_internal.h"
 #include "alora_attention.h"
+#include <new>
 #include <vector>
 
 namespace alora {
@@ -385,6 +386,7 @@ int alora_paged_attention_validate(const int32_t *block_tables, const int32_t *t
     if (dims->n_tokens == 0) return ALORA_OK;
     if (!block_tables || !token_seq_ids || !token_positions) return ALORA_EINVAL;
     const size_t T = (size_t)dims->n_tokens, nt = (size_t)dims->n_seqs * (size_t)dims->max_blocks;
+    try {
     std::vector<int32_t> seq(T), pos(T), bt(nt);
     hipError_t e = hipDeviceSynchronize();
     if (!e) e = hipMemcpy(seq.data(), token_seq_ids, T * sizeof(int32_t), hipMemcpyDeviceToHost);
@@ -408,6 +410,9 @@ int alora_paged_attention_validate(const int32_t *block_tables, const int32_t *t
         }
     }
     return ALORA_OK;
+    } catch (const std::bad_alloc &) {
+        return ALORA_ENOMEM;
+    }
 }
 
 }  // extern "C"

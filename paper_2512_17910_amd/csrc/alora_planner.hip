@@ -134,14 +134,19 @@ int alora_planner_create(int32_t block_size, int64_t n_blocks, alora_planner **o
     *out = nullptr;
     if (block_size <= 0 || n_blocks < 0 || n_blocks > 0x7fffffff) return ALORA_EINVAL;
     alora_planner *p = new (std::nothrow) alora_planner;
-    if (!p) return ALORA_EINVAL;
-    p->bs = block_size;
-    p->n_blocks = n_blocks;
-    p->hash_of.assign((size_t)n_blocks, 0);
-    p->keyed.assign((size_t)n_blocks, 0);
-    p->ref.assign((size_t)n_blocks, 0);
-    p->prev.assign((size_t)n_blocks, -1);
-    p->next.assign((size_t)n_blocks, -1);
+    if (!p) return ALORA_ENOMEM;
+    try {
+        p->bs = block_size;
+        p->n_blocks = n_blocks;
+        p->hash_of.assign((size_t)n_blocks, 0);
+        p->keyed.assign((size_t)n_blocks, 0);
+        p->ref.assign((size_t)n_blocks, 0);
+        p->prev.assign((size_t)n_blocks, -1);
+        p->next.assign((size_t)n_blocks, -1);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return ALORA_ENOMEM;
+    }
     for (int64_t b = 0; b < n_blocks; ++b) p->push_back_free((int32_t)b);
     *out = p;
     return ALORA_OK;
@@ -160,6 +165,7 @@ int alora_planner_admit(alora_planner *p, int64_t req_id, const int32_t *token_i
     if (!p || !token_ids || n_tokens < 1 || adapter_id < -1 || activation_start < 0 || !batch_ok(batch))
         return ALORA_EINVAL;
     if (p->reqs.count(req_id)) return ALORA_EINVAL;
+    try {   // everything that allocates happens before the pool is touched
     Request r;
     r.tokens.assign(token_ids, token_ids + n_tokens);
     r.adapter = adapter_id;
@@ -181,6 +187,8 @@ int alora_planner_admit(alora_planner *p, int64_t req_id, const int32_t *token_i
     const int64_t rows = n - hit * bs;
     if (need > p->n_free - reuse_from_pool) return ALORA_ENOBLOCKS;
     if (rows > batch->row_cap - batch->n_rows || batch->n_segs >= batch->seg_cap) return ALORA_ESHAPE;
+    r.table.reserve((size_t)(hit + need));
+    auto ins = p->reqs.emplace(req_id, Request());
     // nothing can fail from here on
     for (int32_t b : reuse) {
         if (p->ref[b] == 0) p->unlink_free(b);
@@ -195,8 +203,11 @@ int alora_planner_admit(alora_planner *p, int64_t req_id, const int32_t *token_i
     r.keyed = (int32_t)hit;
     emit_rows(p, r, hit * bs, batch);
     if (cached_tokens) *cached_tokens = (int32_t)(hit * bs);
-    p->reqs.emplace(req_id, std::move(r));
+    ins.first->second = std::move(r);
     return ALORA_OK;
+    } catch (const std::bad_alloc &) {
+        return ALORA_ENOMEM;
+    }
 }
 
 int alora_planner_append(alora_planner *p, int64_t req_id, const int32_t *new_token_ids, int32_t n_new,
@@ -211,7 +222,12 @@ int alora_planner_append(alora_planner *p, int64_t req_id, const int32_t *new_to
     const int64_t need = (total + bs - 1) / bs - (int64_t)r.table.size();
     if (need > p->n_free) return ALORA_ENOBLOCKS;
     if (n_new > batch->row_cap - batch->n_rows || batch->n_segs >= batch->seg_cap) return ALORA_ESHAPE;
-    r.tokens.insert(r.tokens.end(), new_token_ids, new_token_ids + n_new);
+    try {   // allocate first, then touch the pool
+        r.table.reserve(r.table.size() + (size_t)std::max<int64_t>(need, 0));
+        r.tokens.insert(r.tokens.end(), new_token_ids, new_token_ids + n_new);
+    } catch (const std::bad_alloc &) {
+        return ALORA_ENOMEM;
+    }
     for (int64_t i = 0; i < need; ++i) {
         const int32_t b = p->take_free();
         p->ref[b] = 1;
@@ -227,15 +243,19 @@ int alora_planner_commit(alora_planner *p, int64_t req_id)
     auto it = p->reqs.find(req_id);
     if (it == p->reqs.end()) return ALORA_EINVAL;
     Request &r = it->second;
-    p->hash_full_blocks(r);
-    for (int64_t b = r.keyed; b < (int64_t)r.hashes.size(); ++b) {
-        const int32_t blk = r.table[b];
-        // an equal block registered by another request in the meantime keeps the entry
-        if (!p->keyed[blk] && !p->block_of.count(r.hashes[b])) {
-            p->block_of.emplace(r.hashes[b], blk);
-            p->hash_of[blk] = r.hashes[b];
-            p->keyed[blk] = 1;
+    try {   // a failed allocation leaves the blocks registered so far registered; the call can be repeated
+        p->hash_full_blocks(r);
+        for (int64_t b = r.keyed; b < (int64_t)r.hashes.size(); ++b) {
+            const int32_t blk = r.table[b];
+            // an equal block registered by another request in the meantime keeps the entry
+            if (!p->keyed[blk] && !p->block_of.count(r.hashes[b])) {
+                p->block_of.emplace(r.hashes[b], blk);
+                p->hash_of[blk] = r.hashes[b];
+                p->keyed[blk] = 1;
+            }
         }
+    } catch (const std::bad_alloc &) {
+        return ALORA_ENOMEM;
     }
     r.keyed = (int32_t)r.hashes.size();
     return ALORA_OK;

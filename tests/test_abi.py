@@ -38,7 +38,7 @@ def test_header_constants_match_binding():
     for name in ("ALORA_F32", "ALORA_BF16", "ALORA_MAX_ADAPTERS", "ALORA_MAX_RANK", "ALORA_OK"):
         m = re.search(rf"#define {name} \(?(-?\d+)\)?", src)
         assert m and int(m.group(1)) == getattr(ab, name)
-    for name in ("ALORA_EINVAL", "ALORA_ESHAPE", "ALORA_EWORKSPACE", "ALORA_EHIP", "ALORA_EDATA"):
+    for name in ("ALORA_EINVAL", "ALORA_ESHAPE", "ALORA_EWORKSPACE", "ALORA_EHIP", "ALORA_EDATA", "ALORA_ENOMEM"):
         m = re.search(rf"#define {name} \((-?\d+)\)", src)
         assert m and int(m.group(1)) == getattr(ab, name)
 
