@@ -23,7 +23,7 @@
  * int32 [n_seqs, max_blocks], entries past a sequence's length are never read.  All pointers are
  * DEVICE pointers, owned by the caller, 16-byte aligned; q/k_cache/v_cache/out have the dtype of
  * dims->dtype (bf16 or fp32); scores, softmax and the weighted sum are fp32, the output is rounded
- * once.  out may not alias q.
+ * once; scaled scores below -1e30 (in units of log2) weigh nothing.  out may not alias q.
  *
  * Limits: head_dim in {64, 128}; n_q_heads / n_kv_heads in {1, 2, 4, 8}; block_size >= 1;
  * n_tokens * n_kv_heads <= 2^31 - 1; n_slots <= 2^31 - 1.  One workgroup per (row, K/V head): meant for decode-sized

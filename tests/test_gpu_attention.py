@@ -77,6 +77,16 @@ def test_long_contexts_and_explicit_scale(dtype):
     assert maxnorm_rel(out, d.oracle(scale=0.05)) <= TOL[dtype]
 
 
+def test_contexts_of_sixteen_thousand_positions():
+    """The long-context shape of the reader's benchmark (--long): 32 query / 8 K/V heads of 128, contexts
+    of 16384 and 8193 positions, every output element against the oracle."""
+    c = wl.attention_case("16k", "bf16", [16384, 8193, 12000], [1, 2, 1], 32, 8, 128, 16, seed=wl.SEED ^ 91)
+    d = DeviceCase(c)
+    out = to_f64(d.run())
+    assert np.isfinite(out).all()
+    assert maxnorm_rel(out, d.oracle()) <= TOL["bf16"]
+
+
 def test_peaked_scores_do_not_overflow():
     """Large score ranges: keys scaled so that scores span hundreds; the running maximum keeps every power
     of two in range."""
