@@ -68,6 +68,23 @@ int alora_paged_attention(const void *q, const void *k_cache, const void *v_cach
                           const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                           const alora_attn_dims *dims, void *hip_stream);
 
+/*
+ * The same computation for batches too small to fill the chip with one workgroup per (row, K/V head)
+ * -- a few sequences with long contexts, the shape of an adapter evaluated on one long conversation
+ * (Sec. 4.2): every row's context is cut into parts, one workgroup each (about 1024 workgroups, at
+ * most 32 parts), the parts leave (running maximum, sum of weights, unnormalised output) in the
+ * workspace and a second kernel combines them in part order.  Results equal those of
+ * alora_paged_attention up to fp32 summation order and do not depend on timing.
+ *   workspace  device, 16-byte aligned, >= alora_paged_attention_workspace_bytes() bytes (0 when the
+ *              batch is large enough for one part: then this IS alora_paged_attention and the
+ *              workspace may be NULL); contents on entry irrelevant; calls that share it must be
+ *              stream-ordered.  Too small or misaligned: ALORA_EWORKSPACE.
+ */
+int alora_paged_attention_workspace_bytes(const alora_attn_dims *dims, size_t *out_bytes);
+int alora_paged_attention_split(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
+                                const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Host-side check of the index data of a call (synchronous; device pointers): every sequence id in
  * [0, n_seqs), every position in [0, max_blocks * block_size), every table entry a row's context
  * reaches in [0, n_slots / block_size).  ALORA_OK, ALORA_EDATA, or an argument error. */

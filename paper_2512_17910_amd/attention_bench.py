@@ -28,6 +28,10 @@ def main() -> None:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--long", action="store_true", help="contexts of 8k-16k positions on 64 sequences instead")
+    ap.add_argument("--few", action="store_true",
+                    help="8 sequences with contexts of 32k-64k positions (an adapter evaluated on a few long "
+                         "conversations), through alora_paged_attention_split; --single-pass times the plain call on it")
+    ap.add_argument("--single-pass", action="store_true")
     args = ap.parse_args()
 
     import torch
@@ -36,7 +40,11 @@ def main() -> None:
 
     dev = "cuda"
     Hq, Hkv, D, bs = 32, 8, 128, 16
-    if args.long:
+    if args.few:
+        rng = np.random.default_rng(13)
+        lens = rng.integers(32768, 65537, 8)
+        name = "decode-8x64k"
+    elif args.long:
         rng = np.random.default_rng(12)
         lens = rng.integers(8192, 16385, 64)
         name = "decode-64x16k"
@@ -46,7 +54,7 @@ def main() -> None:
         name = "cfg3-8b-decode"
     n_seq = len(lens)
     nb = (lens + bs - 1) // bs
-    n_blocks = int(nb.sum()) + 8 if args.long else n_seq * (2048 // bs)
+    n_blocks = int(nb.sum()) + 8 if (args.long or args.few) else n_seq * (2048 // bs)
     perm = np.random.default_rng(5).permutation(n_blocks).astype(np.int32)
     bt = np.full((n_seq, int(nb.max())), -1, np.int32)
     o = 0
@@ -66,6 +74,10 @@ def main() -> None:
     assert ab.alora_paged_attention_validate(bt_d, seq_d, pos_d, dims) == ab.ALORA_OK
 
     call = lambda: ab.alora_paged_attention(q, kc, vc, bt_d, seq_d, pos_d, out, dims)
+    if args.few and not args.single_pass:
+        ws = torch.empty(max(ab.alora_paged_attention_workspace_bytes(dims), 16), dtype=torch.uint8, device=dev)
+        call = lambda: ab.alora_paged_attention_split(q, kc, vc, bt_d, seq_d, pos_d, out, dims, ws)
+        name += "-split"
     for _ in range(args.warmup):
         call()
     torch.cuda.synchronize()

@@ -17,6 +17,7 @@
 #include "alora_internal.h"
 #include "alora_attention.h"
 #include <new>
+#include <algorithm>
 #include <vector>
 
 namespace alora {
@@ -28,6 +29,8 @@ struct AttnArgs {
     int T, Hq, Hkv, n_seqs, max_blocks, bs, bs_shift;
     long long n_slots;
     float scale_log2e;   // scale * log2(e): the softmax runs on powers of two
+    int splits;          // parts a row's context is cut into (one workgroup each); > 1: partials go to `part`
+    float *part;         // [T][Hq][splits][D + 2]: running maximum, sum of weights, unnormalised weighted V
 };
 
 template <int CTRL>
@@ -118,7 +121,9 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     __shared__ float sm[4][G], sl[4][G];
     __shared__ float sacc[4][G][D];
 
-    const int t = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
+    // workgroup -> (row, K/V head, part of the context)
+    const int rh = (int)blockIdx.x / a.splits, sp = (int)blockIdx.x - rh * a.splits;
+    const int t = rh / a.Hkv, hk = rh % a.Hkv;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int grp = lane / LPP, c = lane % LPP;
 
@@ -127,6 +132,13 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     int n_ctx = 0;
     if (sq >= 0 && sq < a.n_seqs && p >= 0) n_ctx = (int)(p + 1ll < cap ? p + 1ll : cap);
     const int32_t *bt = a.bt + (size_t)(n_ctx ? sq : 0) * a.max_blocks;
+    // this workgroup's part of the context: whole blocks of BLK positions, the same number for every part
+    int jbeg = 0;
+    if (a.splits > 1) {
+        const int per = ((n_ctx + a.splits * BLK - 1) / (a.splits * BLK)) * BLK;
+        jbeg = min(n_ctx, sp * per);
+        n_ctx = min(n_ctx, jbeg + per);
+    }
     const int Nkv = a.Hkv * D;
     const int col = hk * D + 8 * c;
     const int jl = wave * PPW + grp;   // this lane group's position inside a step
@@ -241,10 +253,10 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     // the block after it are in flight.
     int blkA[U], blkB[U];
     Raw8<BF16> krA[U], vrA[U], krB[U], vrB[U];
-    lookup(0, blkA);
-    unsigned okA = fetch(0, blkA, krA, vrA), okB;
-    lookup(BLK, blkB);
-    for (int j0 = 0; j0 < n_ctx; j0 += 2 * BLK) {
+    lookup(jbeg, blkA);
+    unsigned okA = fetch(jbeg, blkA, krA, vrA), okB;
+    lookup(jbeg + BLK, blkB);
+    for (int j0 = jbeg; j0 < n_ctx; j0 += 2 * BLK) {
         okB = fetch(j0 + BLK, blkB, krB, vrB);
         lookup(j0 + 2 * BLK, blkA);
         consume(krA, vrA, okA);
@@ -295,6 +307,12 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
             L += sl[w][g] * f;
             o += sacc[w][g][dd] * f;
         }
+        if (a.splits > 1) {   // this part's (maximum, sum, unnormalised output); the merge kernel finishes
+            float *pp = a.part + (((size_t)t * a.Hq + (size_t)hk * G + g) * a.splits + sp) * (D + 2);
+            if (dd == 0) { pp[0] = M; pp[1] = L; }
+            pp[2 + dd] = o;
+            continue;
+        }
         const float y = L > 0.f ? o / L : 0.f;
         const size_t at = ((size_t)t * a.Hq + (size_t)hk * G + g) * D + dd;
         if (BF16) ((bf16_t *)a.out)[at] = (bf16_t)f32_to_bf16_bits(y);
@@ -302,15 +320,41 @@ __global__ __launch_bounds__(256) void paged_attention_kernel(AttnArgs a)
     }
 }
 
+// Second pass of a split call: the parts of a (row, query head) are combined in part order.
+template <int D, bool BF16>
+__global__ __launch_bounds__(D) void paged_attention_merge_kernel(const float *__restrict__ part, void *__restrict__ out, int splits)
+{
+    const size_t rh = blockIdx.x;   // row * Hq + query head
+    const int dd = threadIdx.x;
+    const float *pp = part + rh * splits * (D + 2);
+    float M = M_FLOOR;
+    for (int s2 = 0; s2 < splits; ++s2) M = fmaxf(M, pp[(size_t)s2 * (D + 2)]);
+    float L = 0.f, o = 0.f;
+    for (int s2 = 0; s2 < splits; ++s2) {
+        const float *q2 = pp + (size_t)s2 * (D + 2);
+        const float f = __builtin_amdgcn_exp2f(q2[0] - M);
+        L += q2[1] * f;
+        o += q2[2 + dd] * f;
+    }
+    const float y = L > 0.f ? o / L : 0.f;
+    if (BF16) ((bf16_t *)out)[rh * D + dd] = (bf16_t)f32_to_bf16_bits(y);
+    else ((float *)out)[rh * D + dd] = y;
+}
+
 template <int D, int G>
 static void launch_dg(const AttnArgs &a, bool bf16, hipStream_t st)
 {
-    const dim3 grid((unsigned)a.T * (unsigned)a.Hkv);
+    const dim3 grid((unsigned)a.T * (unsigned)a.Hkv * (unsigned)a.splits);
     const bool pow2 = a.bs_shift >= 0;
     if (bf16 && pow2) hipLaunchKernelGGL((paged_attention_kernel<D, G, true, true>), grid, dim3(256), 0, st, a);
     else if (bf16) hipLaunchKernelGGL((paged_attention_kernel<D, G, true, false>), grid, dim3(256), 0, st, a);
     else if (pow2) hipLaunchKernelGGL((paged_attention_kernel<D, G, false, true>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((paged_attention_kernel<D, G, false, false>), grid, dim3(256), 0, st, a);
+    if (a.splits > 1) {
+        const dim3 mgrid((unsigned)a.T * (unsigned)a.Hq);
+        if (bf16) hipLaunchKernelGGL((paged_attention_merge_kernel<D, true>), mgrid, dim3(D), 0, st, a.part, a.out, a.splits);
+        else hipLaunchKernelGGL((paged_attention_merge_kernel<D, false>), mgrid, dim3(D), 0, st, a.part, a.out, a.splits);
+    }
 }
 
 template <int D>
@@ -340,17 +384,68 @@ static int check_dims(const alora_attn_dims *d)
     return ALORA_OK;
 }
 
+// Parts a row's context is cut into so that a small batch still fills the chip: about 1024 workgroups,
+// at most 32 parts, one part when (rows x K/V heads) already gives that many.
+static int plan_splits(const alora_attn_dims *d)
+{
+    const long long wgs = (long long)d->n_tokens * d->n_kv_heads;
+    if (wgs <= 0 || wgs >= 1024) return 1;
+    return (int)std::min<long long>(32, (1024 + wgs - 1) / wgs);
+}
+
+static size_t split_bytes(const alora_attn_dims *d)
+{
+    const int sp = plan_splits(d);
+    if (sp <= 1) return 0;
+    return (size_t)d->n_tokens * d->n_q_heads * sp * (d->head_dim + 2) * sizeof(float);
+}
+
+static int run(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+               const int32_t *token_seq_ids, const int32_t *token_positions, void *out, const alora_attn_dims *dims,
+               void *workspace, size_t workspace_bytes, bool split, void *hip_stream);
+
 }  // namespace alora
 
 extern "C" {
+
+int alora_paged_attention_workspace_bytes(const alora_attn_dims *dims, size_t *out_bytes)
+{
+    using namespace alora;
+    if (!out_bytes) return ALORA_EINVAL;
+    const int st = check_dims(dims);
+    if (st) return st;
+    *out_bytes = split_bytes(dims);
+    return ALORA_OK;
+}
+
+int alora_paged_attention_split(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
+                                const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, workspace,
+                      workspace_bytes, true, hip_stream);
+}
 
 int alora_paged_attention(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                           const alora_attn_dims *dims, void *hip_stream)
 {
-    using namespace alora;
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0, false,
+                      hip_stream);
+}
+
+}  // extern "C"
+
+namespace alora {
+
+static int run(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+               const int32_t *token_seq_ids, const int32_t *token_positions, void *out, const alora_attn_dims *dims,
+               void *workspace, size_t workspace_bytes, bool split, void *hip_stream)
+{
     const int st = check_dims(dims);
     if (st) return st;
+    const int splits = split ? plan_splits(dims) : 1;
+    if (splits > 1 && (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < split_bytes(dims))) return ALORA_EWORKSPACE;
     if (dims->n_tokens == 0) return ALORA_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !token_seq_ids || !token_positions || !out) return ALORA_EINVAL;
     if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) return ALORA_EINVAL;
@@ -365,6 +460,8 @@ int alora_paged_attention(const void *q, const void *k_cache, const void *v_cach
     for (int sft = 0; sft < 31; ++sft)
         if ((1 << sft) == dims->block_size) a.bs_shift = sft;
     a.n_slots = dims->n_slots;
+    a.splits = splits;
+    a.part = (float *)workspace;
     const float scale = dims->scale > 0.f ? dims->scale : 1.0f / sqrtf((float)dims->head_dim);
     a.scale_log2e = scale * 1.4426950408889634f;
     const bool bf16 = dims->dtype == ALORA_BF16;
@@ -376,6 +473,10 @@ int alora_paged_attention(const void *q, const void *k_cache, const void *v_cach
     if (e) { note_hip_error((int)e); return ALORA_EHIP; }
     return ALORA_OK;
 }
+
+}  // namespace alora
+
+extern "C" {
 
 int alora_paged_attention_validate(const int32_t *block_tables, const int32_t *token_seq_ids,
                                    const int32_t *token_positions, const alora_attn_dims *dims)

@@ -188,3 +188,43 @@ def test_decode_batch_at_benchmark_size_on_sampled_rows():
     assert np.isfinite(out).all()
     rows = np.r_[np.argmax(lens), np.argmin(lens), rng.choice(256, 22, replace=False)]
     assert maxnorm_rel(out[rows], d.oracle(rows=rows)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype,head_dim,group", [("bf16", 128, 4), ("f32", 64, 2), ("bf16", 64, 8), ("bf16", 128, 1)])
+def test_split_contexts_match_the_oracle_and_the_single_pass(dtype, head_dim, group):
+    """Few rows: every context is cut into up to 32 parts that a second kernel combines.  Ragged contexts
+    (shorter than one part, exactly on part boundaries, thousands of positions), against the oracle and,
+    to summation order, against the one-workgroup-per-row call; two calls give the same bits."""
+    lens = [1, 3, 64, 65, 4096, 4097, 1000, 2048 * 3 + 17]
+    c = wl.attention_case(f"split-{dtype}-{head_dim}-{group}", dtype, lens, [1, 2, 1, 1, 1, 3, 1, 1], 2 * group, 2, head_dim,
+                          16, seed=wl.SEED ^ (77 + group))
+    d = DeviceCase(c)
+    nbytes = ab.alora_paged_attention_workspace_bytes(d.dims)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ab.alora_paged_attention_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws)
+    torch.cuda.synchronize()
+    got = to_f64(d.out)
+    bits = raw_bits(d.out).copy()
+    assert np.isfinite(got).all()
+    assert maxnorm_rel(got, d.oracle()) <= TOL[dtype]
+    single = to_f64(d.run())
+    assert maxnorm_rel(got, single) <= TOL[dtype]
+    ws.fill_(0xFF)                                  # leftovers in the workspace do not matter
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_bits(d.out), bits)
+    with pytest.raises(ab.AloraError):
+        ab.alora_paged_attention_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws[: nbytes - 16])
+
+
+def test_split_call_on_a_large_batch_is_the_single_pass():
+    c = wl.attention_case("split-large", "bf16", _ragged_lens(4, 140, 300), [1] * 140, 32, 8, 128, 16, seed=wl.SEED ^ 23)
+    d = DeviceCase(c)
+    assert ab.alora_paged_attention_workspace_bytes(d.dims) == 0          # 140 rows x 8 K/V heads fill the chip
+    first = raw_bits(d.run()).copy()
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_bits(d.out), first)
