@@ -2,24 +2,28 @@
 // expand, the per-row activation select, the q_out store and the paged K/V store in one pass.
 //
 // Per 256(token) x 256|192|128(feature) tile, one workgroup of four wavefronts (one per SIMD):
-//   1. classify the tile's rows (App. B mask); list the adapters its adapted rows use
+//   1. fetch the tile's rows' effective adapters (the grouping step's classification, App. B mask)
+//      and cache slots; list the adapters its adapted rows use
 //   2. expand first: for each such adapter a, accumulate [S_hi | S_lo](rows of a, else 0) . [B_a ; B_a]
-//      as extra K-slices of the same MFMA loop, then zero the accumulators of rows that are not
-//      adapted (a select, not a multiply: adapter data never reaches a base row)
+//      32 k at a time through the one LDS stage the base prologue leaves free, then zero the
+//      accumulators of rows that are not adapted (a select, not a multiply: adapter data never
+//      reaches a base row)
 //   3. base GEMM over the hidden dimension: rows that are not adapted see exactly the
 //      instruction sequence of a call without adapters, so they come out bit-identical to it
 //   4. round once to bf16 and store: columns [0,Nq) to q_out, K and V columns to the slot the
 //      row maps to (rows with slot -1 write no K/V)
+// Small-batch (split) mode stops after 3 over its range of the hidden dimension and stores fp32
+// partials; for batches of at most 256 rows extra workgroups behind the projection's own classify,
+// group and shrink the batch (alora_group_small.h, alora_shrink_rows.h) out of the same LDS stages.
 //
 // Data movement (gfx950):
 //   - global -> LDS with buffer loads that write LDS directly (no VGPR staging); the buffer
 //     descriptor's range check returns zeros for token rows past T, masked lanes get an
 //     out-of-range offset.
-//   - the K dimension runs through a ring of four 32 KB LDS stages, 32 k per stage.  The slices a
-//     tile consumes form one sequence: first the expand slices (one or more per adapter present in
-//     the tile), then the base slices.  While slice i is multiplied, the first fragments of slice
-//     i+1 are already fetched from LDS, and slices i+2 and i+3 are in flight from memory; the
-//     copies of slice i+3 are issued one per three MFMAs, which keeps the demand on the vector
+//   - the K dimension runs through a ring of LDS stages, 32 k per stage: four 32 KB stages, six
+//     24 KB stages for the 128-wide tile.  While slice i is multiplied, the first fragments of
+//     slice i+1 are already fetched from LDS and the slices after it are in flight from memory;
+//     their copies are issued one per two or three MFMAs, which keeps the demand on the vector
 //     memory pipe (64 B/clk per CU) uniform.  One barrier per slice, placed where the MFMAs that
 //     follow it already have their operands in registers.
 //   - token tile in LDS: [row][32 k], 16-byte chunks XOR-swizzled by (row/4)%4, read with
