@@ -22,7 +22,7 @@ static Profile g_prof;
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t active, aeff, perm, offsets, S, blocktab, items, counters, hist, partial, total;
+    size_t active, aeff, perm, offsets, S, blocktab, items, counters, block_rows, hist, partial, total;
     int n_blocks, n_items;
 };
 
@@ -66,6 +66,7 @@ static Layout make_layout(const alora_dims *d)
     l.n_items = d->dtype == ALORA_BF16 ? shrink_items(d->T, d->n_adapters) : 0;
     l.items = o;    o += up256(16 * (size_t)l.n_items);
     l.counters = o; o += up256(4 * (size_t)l.n_items);   // one per block; indexed below n_items
+    l.block_rows = o; o += up256(d->dtype == ALORA_BF16 && d->T <= 256 ? 4 * 32 * (size_t)l.n_blocks : 0);
     l.hist = o;     o += up256(group_hist_bytes(d->T));
     l.partial = o;
     if (d->dtype == ALORA_BF16) o += up256(gemm_partial_bytes(d->T, d->hidden, (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim));
@@ -101,6 +102,7 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
     f.items = work_list ? (int4 *)(b + l.items) : nullptr;
     f.counters = work_list ? (int32_t *)(b + l.counters) : nullptr;
     f.n_items = work_list ? l.n_items : 0;
+    f.block_rows = (d->dtype == ALORA_BF16 && d->T <= 256) ? (int32_t *)(b + l.block_rows) : nullptr;
     f.partial = (float *)(b + l.partial);
     f.n_blocks = l.n_blocks;
     f.stream = (hipStream_t)stream;

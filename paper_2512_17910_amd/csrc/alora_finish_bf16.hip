@@ -28,6 +28,7 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
                                                            const void *__restrict__ S_any, int s_splits, PtrTable B,
                                                            RankTable ranks, const bf16_t *__restrict__ bias,
                                                            const int32_t *__restrict__ perm,
+                                                           const int32_t *__restrict__ block_rows,
                                                            const int4 *__restrict__ blocktab,
                                                            const int64_t *__restrict__ slot, bf16_t *__restrict__ q,
                                                            bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int T, int Nq,
@@ -37,6 +38,10 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
     __shared__ float s_lds[32][ALORA_MAX_RANK + 1];
     __shared__ __attribute__((aligned(16))) bf16_t b_lds[ALORA_MAX_RANK][FIN_COLS];
 
+    const int tid0 = threadIdx.x;
+    // row ids straight from the per-entry list when there is one: the load does not wait for the entry
+    int t_direct = -1;
+    if (block_rows) t_direct = block_rows[32 * blockIdx.x + (tid0 >> 5)];
     const int4 entry = blocktab[blockIdx.x];
     const int a = entry.x, j0 = entry.y, cnt = entry.z;
     if (a < 0) return;  // unused table entry; uniform across the workgroup
@@ -47,7 +52,7 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
     const bool adapted = a < L;
     const int ra = adapted ? ranks.r[a] : 0;   // this group's rank; S and B_a rows beyond it do not exist
     const int i = tid >> 5, c = tid & 31, n = n0 + 8 * c;
-    int t = i < cnt ? perm[j0 + i] : -1;
+    int t = block_rows ? (i < cnt ? t_direct : -1) : (i < cnt ? perm[j0 + i] : -1);
     if (t >= T) t = -1;
     const bool live = t >= 0 && n < N;
 
@@ -142,24 +147,24 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
 }
 
 template <int SPLITS>
-static void launch_finish(const Fwd &f, const PtrTable &B, int s_splits)
+static void launch_finish(const Fwd &f, const PtrTable &B, int s_splits, const int32_t *block_rows)
 {
     const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
     hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
-                       f.S, s_splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
+                       f.S, s_splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, block_rows, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
                        (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
 }
 
-int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits)
+int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits, const int32_t *block_rows)
 {
     switch (splits) {
-    case 2: launch_finish<2>(f, B, s_splits); break;
-    case 3: launch_finish<3>(f, B, s_splits); break;
-    case 4: launch_finish<4>(f, B, s_splits); break;
-    case 5: launch_finish<5>(f, B, s_splits); break;
-    case 6: launch_finish<6>(f, B, s_splits); break;
-    case 7: launch_finish<7>(f, B, s_splits); break;
-    case 8: launch_finish<8>(f, B, s_splits); break;
+    case 2: launch_finish<2>(f, B, s_splits, block_rows); break;
+    case 3: launch_finish<3>(f, B, s_splits, block_rows); break;
+    case 4: launch_finish<4>(f, B, s_splits, block_rows); break;
+    case 5: launch_finish<5>(f, B, s_splits, block_rows); break;
+    case 6: launch_finish<6>(f, B, s_splits, block_rows); break;
+    case 7: launch_finish<7>(f, B, s_splits, block_rows); break;
+    case 8: launch_finish<8>(f, B, s_splits, block_rows); break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();

@@ -596,7 +596,7 @@ static void launch_ntw(const GemmArgs &g, const PtrTable &B, const PtrTable &A, 
 // on workgroups behind its own (the projection of such a batch does not fill every compute unit).
 bool prep_in_projection(const Fwd &f)
 {
-    if (f.dtype != ALORA_BF16 || f.L <= 0 || f.T <= 0 || f.T > GROUP_SMALL_ROWS || f.r > 32) return false;
+    if (f.dtype != ALORA_BF16 || f.L <= 0 || f.T <= 0 || f.T > GROUP_SMALL_ROWS || f.r > 32 || !f.block_rows) return false;
     const GemmPlan plan = plan_gemm(f.T, f.H, f.N);
     return plan.splits > 1 && plan.ntw == 2;
 }
@@ -625,7 +625,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEven
     g.prep_kper = ((f.H / 64 + want - 1) / want) * 64;
     g.prep_ranges = (f.H + g.prep_kper - 1) / g.prep_kper;
     g.prep_wgs = prep ? f.n_blocks * g.prep_ranges : 0;
-    g.prep = GroupSmallArgs{f.aid, f.seg, f.pos, f.start, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks};
+    g.prep = GroupSmallArgs{f.aid, f.seg, f.pos, f.start, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks, f.block_rows};
     g.S_out = f.S;
     if (plan.ntw == 4) launch_ntw<4>(g, B, A, f.stream);
     else if (plan.ntw == 3) launch_ntw<3>(g, B, A, f.stream);
@@ -633,7 +633,8 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEven
     int e = (int)hipGetLastError();
     if (!e && after_projection) e = (int)hipEventRecord(after_projection, f.stream);
     if (e || plan.splits == 1) return e;
-    return launch_finish_bf16(f, B, plan.splits, prep ? g.prep_ranges : plan_shrink(f.T, f.H, f.N, f.L, f.r).splits);
+    return launch_finish_bf16(f, B, plan.splits, prep ? g.prep_ranges : plan_shrink(f.T, f.H, f.N, f.L, f.r).splits,
+                              prep ? f.block_rows : nullptr);
 }
 
 }  // namespace alora

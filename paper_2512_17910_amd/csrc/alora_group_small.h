@@ -24,6 +24,7 @@ struct GroupSmallArgs {
     int32_t *perm, *offsets;
     int4 *blocktab;
     int n_blocks;
+    int32_t *block_rows;   // [n_blocks][32] row ids per entry, -1 padded
 };
 
 // Entry `e` of the block table of the batch: returns the group in `grp` (-1: unused entry), the
@@ -80,6 +81,7 @@ __device__ __forceinline__ const int *group_small(const GroupSmallArgs &ga, int 
     if (!write) return rows;
     if (e < ga.n_blocks && tid == 0) ga.blocktab[e] = grp >= 0 ? make_int4(grp, j0, cnt, 0) : make_int4(-1, 0, 0, 0);
     if (tid < cnt) ga.perm[j0 + tid] = rows[tid];
+    if (e < ga.n_blocks && tid < 32) ga.block_rows[32 * e + tid] = rows[tid];
     if (e == 0 && tid <= L + 1) ga.offsets[tid] = goff[tid];
     if (tid < 32) {
         const int t = 32 * e + tid;

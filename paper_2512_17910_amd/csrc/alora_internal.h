@@ -51,6 +51,8 @@ struct Fwd {
     int4 *items;         // (adapter, first perm index, rows | range width/64 << 8, range | ranges << 4 | block << 8)
     int32_t *counters;   // per block: ranges that have stored their partial (zeroed by the grouping step)
     int n_items;
+    int32_t *block_rows;  // decode-sized bf16 batches: the row ids of every block-table entry, 32 per entry, -1 padded
+                          // (the finishing kernel then needs no look-up through perm)
     hipStream_t stream;
 };
 
@@ -84,7 +86,7 @@ int launch_gemm_f32(const Fwd &f, const PtrTable &B);
 int launch_shrink_bf16(const Fwd &f, const PtrTable &A);
 int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEvent_t after_projection);
 bool prep_in_projection(const Fwd &f);   // grouping and shrink run inside the split projection kernel
-int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits);
+int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits, const int32_t *block_rows);
 struct GemmPlan {
     int ntw;     // 32-wide feature tiles per wavefront (tile width 64 * ntw)
     int splits;  // 1: fused kernel; > 1: split hidden dimension + finishing kernel
