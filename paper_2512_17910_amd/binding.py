@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_graph_destroy.argtypes = [vp]
         L.alora_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp]
         L.alora_paged_attention_validate.argtypes = [vp, vp, vp, ctypes.POINTER(AloraAttnDims)]
+        L.alora_paged_attention_suffix.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp]
         L.alora_paged_attention_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp, sz, vp]
         L.alora_paged_attention_workspace_bytes.argtypes = [ctypes.POINTER(AloraAttnDims), ctypes.POINTER(sz)]
         L.alora_status_string.argtypes = [ctypes.c_int]
@@ -92,7 +93,7 @@ def lib() -> ctypes.CDLL:
         for name in ("alora_qkv_profile_begin", "alora_qkv_profile_end", "alora_qkv_workspace_bytes", "alora_qkv_workspace_layout", "alora_qkv_classify_group",
                      "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version",
                      "alora_qkv_forward_ex", "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy",
-                     "alora_paged_attention", "alora_paged_attention_validate", "alora_paged_attention_split",
+                     "alora_paged_attention", "alora_paged_attention_validate", "alora_paged_attention_split", "alora_paged_attention_suffix",
                      "alora_paged_attention_workspace_bytes"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -307,3 +308,13 @@ def alora_paged_attention_split(q, k_cache, v_cache, block_tables, token_seq_ids
                                           workspace.numel() if workspace is not None else 0, _stream_handle(stream))
     if s:
         raise AloraError(s, "alora_paged_attention_split")
+
+
+def alora_paged_attention_suffix(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out,
+                                 dims: AloraAttnDims, stream=None) -> None:
+    """alora_paged_attention for the rows of a projected suffix: consecutive rows of a sequence share the loads
+    of their context (bf16, head_dim 128)."""
+    s = lib().alora_paged_attention_suffix(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables), _ptr(token_seq_ids),
+                                           _ptr(token_positions), _ptr(out), ctypes.byref(dims), _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_paged_attention_suffix")

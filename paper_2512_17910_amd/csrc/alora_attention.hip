@@ -16,22 +16,13 @@
 // (lane groups by shuffles, wavefronts through LDS), so the result does not depend on timing.
 #include "alora_internal.h"
 #include "alora_attention.h"
+#include "alora_attention_internal.h"
 #include <new>
 #include <algorithm>
 #include <vector>
 
 namespace alora {
 
-struct AttnArgs {
-    const void *q, *kc, *vc;
-    const int32_t *bt, *seq, *pos;
-    void *out;
-    int T, Hq, Hkv, n_seqs, max_blocks, bs, bs_shift;
-    long long n_slots;
-    float scale_log2e;   // scale * log2(e): the softmax runs on powers of two
-    int splits;          // parts a row's context is cut into (one workgroup each); > 1: partials go to `part`
-    float *part;         // [T][Hq][splits][D + 2]: running maximum, sum of weights, unnormalised weighted V
-};
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v)
@@ -402,7 +393,7 @@ static size_t split_bytes(const alora_attn_dims *d)
 
 static int run(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                const int32_t *token_seq_ids, const int32_t *token_positions, void *out, const alora_attn_dims *dims,
-               void *workspace, size_t workspace_bytes, bool split, void *hip_stream);
+               void *workspace, size_t workspace_bytes, int mode, void *hip_stream);
 
 }  // namespace alora
 
@@ -423,14 +414,22 @@ int alora_paged_attention_split(const void *q, const void *k_cache, const void *
                                 const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, workspace,
-                      workspace_bytes, true, hip_stream);
+                      workspace_bytes, 1, hip_stream);
+}
+
+int alora_paged_attention_suffix(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                 const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
+                                 const alora_attn_dims *dims, void *hip_stream)
+{
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0, 2,
+                      hip_stream);
 }
 
 int alora_paged_attention(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                           const alora_attn_dims *dims, void *hip_stream)
 {
-    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0, false,
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0, 0,
                       hip_stream);
 }
 
@@ -440,11 +439,12 @@ namespace alora {
 
 static int run(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                const int32_t *token_seq_ids, const int32_t *token_positions, void *out, const alora_attn_dims *dims,
-               void *workspace, size_t workspace_bytes, bool split, void *hip_stream)
+               void *workspace, size_t workspace_bytes, int mode, void *hip_stream)
 {
     const int st = check_dims(dims);
     if (st) return st;
-    const int splits = split ? plan_splits(dims) : 1;
+    const int splits = mode == 1 ? plan_splits(dims) : 1;
+    if (mode == 2 && (dims->dtype != ALORA_BF16 || dims->head_dim != 128)) return ALORA_ESHAPE;
     if (splits > 1 && (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < split_bytes(dims))) return ALORA_EWORKSPACE;
     if (dims->n_tokens == 0) return ALORA_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !token_seq_ids || !token_positions || !out) return ALORA_EINVAL;
@@ -466,6 +466,11 @@ static int run(const void *q, const void *k_cache, const void *v_cache, const in
     a.scale_log2e = scale * 1.4426950408889634f;
     const bool bf16 = dims->dtype == ALORA_BF16;
     const int G = dims->n_q_heads / dims->n_kv_heads;
+    if (mode == 2) {
+        const int e2 = launch_attention_blocks(a, G, (hipStream_t)hip_stream);
+        if (e2) { note_hip_error(e2); return ALORA_EHIP; }
+        return ALORA_OK;
+    }
     const bool launched = dims->head_dim == 128 ? launch_d<128>(a, G, bf16, (hipStream_t)hip_stream)
                                                 : launch_d<64>(a, G, bf16, (hipStream_t)hip_stream);
     if (!launched) return ALORA_ESHAPE;

@@ -228,3 +228,70 @@ def test_split_call_on_a_large_batch_is_the_single_pass():
     ab.alora_paged_attention_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, None)
     torch.cuda.synchronize()
     assert np.array_equal(raw_bits(d.out), first)
+
+
+def _run_suffix(d):
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_suffix(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims)
+    torch.cuda.synchronize()
+    return d.out
+
+
+@pytest.mark.parametrize("group", [1, 2, 4, 8])
+def test_suffix_rows_share_their_context_and_match_the_oracle(group):
+    """Runs of consecutive rows (projected suffixes of 1..70 rows starting at arbitrary positions), single
+    decode rows in between, contexts from 1 to thousands of positions, block sizes 16 and 5: every row
+    against the oracle; uncovered slots hold NaN."""
+    lens = [1, 40, 333, 64, 2500, 97, 1031]
+    rows = [1, 40, 70, 1, 33, 5, 8]
+    for bs in (16, 5):
+        c = wl.attention_case(f"suffix-g{group}-bs{bs}", "bf16", lens, rows, 2 * group, 2, 128, bs, seed=wl.SEED ^ (300 + group))
+        print(f"[case] {c.name} T={c.T}", flush=True)
+        d = DeviceCase(c)
+        out = to_f64(_run_suffix(d))
+        assert np.isfinite(out).all()
+        assert maxnorm_rel(out, d.oracle()) <= TOL["bf16"]
+
+
+def test_suffix_call_on_a_decode_batch_and_on_interleaved_rows():
+    """No two batch rows continue each other: every row is a block of its own."""
+    rng = np.random.default_rng(5)
+    lens = rng.integers(1, 700, 60)
+    c = wl.attention_case("suffix-decode", "bf16", lens, [1] * 60, 32, 8, 128, 16, seed=wl.SEED ^ 61)
+    d = DeviceCase(c)
+    out = to_f64(_run_suffix(d))
+    assert maxnorm_rel(out, d.oracle()) <= TOL["bf16"]
+    # rows of two sequences interleaved (positions consecutive per sequence, but not in the batch)
+    c2 = wl.attention_case("suffix-interleaved", "bf16", [300, 300], [16, 16], 8, 2, 128, 16, seed=wl.SEED ^ 62)
+    order = np.arange(32).reshape(2, 16).T.reshape(-1)
+    c2.q, c2.token_seq_ids, c2.token_positions = c2.q[order], c2.token_seq_ids[order], c2.token_positions[order]
+    d2 = DeviceCase(c2)
+    out2 = to_f64(_run_suffix(d2))
+    assert maxnorm_rel(out2, d2.oracle()) <= TOL["bf16"]
+
+
+def test_suffix_call_causal_boundaries_bad_indices_and_shapes():
+    c = wl.attention_case("suffix-causal", "bf16", [200, 90], [40, 1], 8, 2, 128, 16, seed=wl.SEED ^ 9)
+    d = DeviceCase(c)
+    base = raw_bits(_run_suffix(d)).copy()
+    assert maxnorm_rel(to_f64(d.out), d.oracle()) <= TOL["bf16"]
+    j = 180
+    slot = int(c.block_tables[0][j // 16]) * 16 + j % 16
+    d.vc[slot] += 1.0
+    d.kc[slot] *= -1.0
+    after = raw_bits(_run_suffix(d))
+    before_rows = np.flatnonzero((c.token_seq_ids == 0) & (c.token_positions < j))
+    after_rows = np.flatnonzero((c.token_seq_ids == 0) & (c.token_positions >= j))
+    assert np.array_equal(after[before_rows], base[before_rows])
+    assert all((after[r] != base[r]).any() for r in after_rows)
+    # a row with a bad sequence id gets zeros, its neighbours are unaffected
+    seq = c.token_seq_ids.copy()
+    seq[10] = 99
+    d.seq.copy_(torch.from_numpy(seq))
+    out = to_f64(_run_suffix(d))
+    assert (out[10] == 0).all() and np.isfinite(out).all()
+    # fp32 and head_dim 64 are not served by this entry point
+    c3 = wl.attention_case("suffix-f32", "f32", [20], [2], 4, 2, 128, 16, seed=wl.SEED ^ 1)
+    d3 = DeviceCase(c3)
+    with pytest.raises(ab.AloraError):
+        ab.alora_paged_attention_suffix(d3.q, d3.kc, d3.vc, d3.bt, d3.seq, d3.pos, d3.out, d3.dims)
