@@ -32,6 +32,10 @@ def main() -> None:
                     help="8 sequences with contexts of 32k-64k positions (an adapter evaluated on a few long "
                          "conversations), through alora_paged_attention_split; --single-pass times the plain call on it")
     ap.add_argument("--single-pass", action="store_true")
+    ap.add_argument("--suffix", type=int, default=0, metavar="ROWS",
+                    help="4 sequences of 16384 positions whose last ROWS positions are query rows (a projected suffix over "
+                         "a cached prefix), through alora_paged_attention_suffix; with --single-pass through the per-row call")
+    ap.add_argument("--decode-through-suffix", action="store_true", help="the default decode batch through the suffix call")
     args = ap.parse_args()
 
     import torch
@@ -40,7 +44,12 @@ def main() -> None:
 
     dev = "cuda"
     Hq, Hkv, D, bs = 32, 8, 128, 16
-    if args.few:
+    rows_per_seq = 1
+    if args.suffix:
+        lens = np.full(4, 16384)
+        rows_per_seq = args.suffix
+        name = f"suffix-4x16384-last{args.suffix}"
+    elif args.few:
         rng = np.random.default_rng(13)
         lens = rng.integers(32768, 65537, 8)
         name = "decode-8x64k"
@@ -54,7 +63,7 @@ def main() -> None:
         name = "cfg3-8b-decode"
     n_seq = len(lens)
     nb = (lens + bs - 1) // bs
-    n_blocks = int(nb.sum()) + 8 if (args.long or args.few) else n_seq * (2048 // bs)
+    n_blocks = int(nb.sum()) + 8 if (args.long or args.few or args.suffix) else n_seq * (2048 // bs)
     perm = np.random.default_rng(5).permutation(n_blocks).astype(np.int32)
     bt = np.full((n_seq, int(nb.max())), -1, np.int32)
     o = 0
@@ -65,15 +74,20 @@ def main() -> None:
     g.manual_seed(1234)
     kc = torch.randn((n_blocks * bs, Hkv * D), device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
     vc = torch.randn((n_blocks * bs, Hkv * D), device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
-    q = torch.randn((n_seq, Hq * D), device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    seq_h = np.repeat(np.arange(n_seq, dtype=np.int32), rows_per_seq)
+    pos_h = np.concatenate([np.arange(l - rows_per_seq, l, dtype=np.int32) for l in lens])
+    q = torch.randn((len(seq_h), Hq * D), device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
     out = torch.empty_like(q)
     bt_d = torch.from_numpy(bt).to(dev)
-    seq_d = torch.arange(n_seq, dtype=torch.int32, device=dev)
-    pos_d = torch.from_numpy((lens - 1).astype(np.int32)).to(dev)
+    seq_d = torch.from_numpy(seq_h).to(dev)
+    pos_d = torch.from_numpy(pos_h).to(dev)
     dims = ab.make_attn_dims(q, kc, bt_d, Hq, Hkv, D, bs)
     assert ab.alora_paged_attention_validate(bt_d, seq_d, pos_d, dims) == ab.ALORA_OK
 
     call = lambda: ab.alora_paged_attention(q, kc, vc, bt_d, seq_d, pos_d, out, dims)
+    if (args.suffix and not args.single_pass) or args.decode_through_suffix:
+        call = lambda: ab.alora_paged_attention_suffix(q, kc, vc, bt_d, seq_d, pos_d, out, dims)
+        name += "-rowblocks"
     if args.few and not args.single_pass:
         ws = torch.empty(max(ab.alora_paged_attention_workspace_bytes(dims), 16), dtype=torch.uint8, device=dev)
         call = lambda: ab.alora_paged_attention_split(q, kc, vc, bt_d, seq_d, pos_d, out, dims, ws)
@@ -90,13 +104,16 @@ def main() -> None:
     per = np.asarray([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)])   # ms, back-to-back launches
     ms = float(ev[0].elapsed_time(ev[-1]) / args.steps)
 
-    ctx_bytes = int(lens.sum()) * 2 * Hkv * D * 2
-    io_bytes = ctx_bytes + 2 * n_seq * Hq * D * 2
-    res = {"metric": "paged-attention reader, context positions/s at 1 MI355X; % HBM GB/s", "value": float(lens.sum()) / (ms * 1e-3),
+    ctx_positions = int((pos_h.astype(np.int64) + 1).sum())          # context positions over all rows
+    ctx_bytes = int(lens.sum()) * 2 * Hkv * D * 2                      # every cached row once
+    io_bytes = ctx_bytes + 2 * len(seq_h) * Hq * D * 2
+    flops = 4.0 * ctx_positions * Hq * D
+    res = {"metric": "paged-attention reader, context positions/s at 1 MI355X; % HBM GB/s", "value": float(ctx_positions) / (ms * 1e-3),
            "unit": "context positions/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "step_us_median": float(np.median(per) * 1e3), "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": name, "rows": n_seq, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "block_size": bs,
-                      "context_positions": int(lens.sum()), "max_context": int(lens.max())},
+           "tflops": flops / (ms * 1e-3) / 1e12,
+           "config": {"workload": name, "rows": int(len(seq_h)), "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "block_size": bs,
+                      "context_positions": ctx_positions, "max_context": int(lens.max())},
            "roofline": {"bound": "hbm", "achieved": io_bytes / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                         "frac": io_bytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None, "kernel": "paged_attention_kernel<128, 4, true, true>",
                         "kernel_ms": ms, "algorithmic_bytes_per_launch": io_bytes}}

@@ -466,7 +466,9 @@ static int run(const void *q, const void *k_cache, const void *v_cache, const in
     a.scale_log2e = scale * 1.4426950408889634f;
     const bool bf16 = dims->dtype == ALORA_BF16;
     const int G = dims->n_q_heads / dims->n_kv_heads;
-    if (mode == 2) {
+    // (the row-block kernel reads one table entry per four aligned positions; other block sizes, and a call
+    // without table or cache, take the per-row kernel)
+    if (mode == 2 && dims->block_size % 4 == 0 && dims->n_seqs >= 1 && dims->max_blocks >= 1 && dims->n_slots >= dims->block_size) {
         const int e2 = launch_attention_blocks(a, G, (hipStream_t)hip_stream);
         if (e2) { note_hip_error(e2); return ALORA_EHIP; }
         return ALORA_OK;

@@ -2,22 +2,23 @@
 // (a projected suffix attending over a cached prefix, Sec. 2.3 / 4.2) are handled by ONE workgroup per
 // K/V head, which loads every cached row once for all of them.  bf16, head_dim 128, on bf16 MFMA.
 //
-// A workgroup owns up to 32 columns (query row, query head of the K/V head's group): 32 / G rows.  Row
-// blocks are cut at multiples of 32 / G of the POSITION, so whether a batch row leads a block is decided
+// A wavefront owns 32 columns (query row, query head of the K/V head's group): 32 / G rows; a workgroup
+// four times that.  Row blocks are cut at multiples of 128 / G of the POSITION, so whether a batch row leads a block is decided
 // from the row before it alone; the workgroups of the other rows exit at once.  A decode batch (every
 // row its own sequence) degenerates to one row per workgroup.
 //
 // Per 32 context positions a wavefront runs two sets of 32x32x16 MFMAs that keep every column in one
 // lane pair from the scores to the output:
-//   scores^T [position x column] = K [position x d] . Q^T [d x column]   K rows loaded straight from the
-//       cache into the A operand (a lane holds 8 consecutive d of one position), Q held in registers;
+//   scores^T [position x column] = K [position x d] . Q^T [d x column]   K rows from the LDS tile into the
+//       A operand (a lane holds 8 consecutive d of one position), Q held in registers;
 //   online softmax down each column: 16 accumulator registers per lane, one exchange between the two
 //       lanes of a column;
 //   out^T [d x column] += V^T [d x position] . P [position x column]   V goes through LDS and comes back
 //       with the transposing LDS load; P is the score accumulator itself, rounded to bf16 -- the B operand
 //       wants, per lane, the positions the accumulator registers of that lane already hold, up to an
 //       exchange of two position bits that is applied to the V rows when they are written to LDS.
-// The four wavefronts take every fourth block of 32 positions and are merged in fixed order at the end.
+// The four wavefronts of a workgroup own 32 columns each (4 x 32 / G consecutive rows) and share the K and
+// V tiles of a block of 32 positions through LDS: every cached row is loaded once per 128 / G query rows.
 #include "alora_attention_internal.h"
 
 namespace alora {
@@ -31,11 +32,11 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 constexpr float AB_NEG_INF = -__builtin_inff();
 constexpr float AB_M_FLOOR = -1.0e30f;   // finite floor of the running maximum (scores below it weigh nothing)
 
-// k..k+3 of this lane's column, then k+4..k+7 (four rows further on)
+// four k of this lane's column, then the four that lie eight rows further on
 __device__ __forceinline__ bf16x8 read_tr_frag(const lds_byte *p, int pitch)
 {
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * pitch));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 8 * pitch));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
@@ -46,41 +47,93 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int G>
-__global__ __launch_bounds__(256) void paged_attention_blocks_kernel(AttnArgs a)
+// 16 bytes straight from global memory into LDS at lds_addr + 16 * lane.  An assembly statement: the
+// kernel orders these copies against its LDS reads itself (wait counts and barriers in the main loop).
+__device__ __forceinline__ void load_lds16(uint32_t lds_addr, const void *p)
 {
-    constexpr int D = 128, RB = 32 / G;   // query rows per workgroup
-    constexpr int VPITCH = 256;           // bytes per position row of the V tile in LDS
-    __shared__ __attribute__((aligned(16))) unsigned char vt[4][32 * VPITCH];   // one V tile per wavefront
-    __shared__ float mrg[3][64][2 + 64];                                        // wavefronts 1..3 hand over to 0
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(p) : "memory");
+}
+__device__ __forceinline__ float max3(float x, float y, float z)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+    return r;
+}
+// lo <- the value the lower 32 lanes hold in x, hi <- the upper 32 lanes' (each in all 64 lanes): one
+// v_permlane32_swap on two copies of x.  Assembly: the builtin of this name returned the first result twice.
+__device__ __forceinline__ void both_halves(float x, float &lo, float &hi)
+{
+    lo = x, hi = x;
+    asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+__device__ __forceinline__ float max_with_other_half(float x)
+{
+    float lo, hi;
+    both_halves(x, lo, hi);
+    return max3(x, lo, hi);
+}
+__device__ __forceinline__ float sum_with_other_half(float x)
+{
+    float lo, hi;
+    both_halves(x, lo, hi);
+    return lo + hi;
+}
+
+// what a lane loads for a position that is not part of the context (the weighted sum multiplies it by 0)
+__device__ const uint32_t ab_zero_chunk[4] = {0u, 0u, 0u, 0u};
+
+template <int G>
+__global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs a)
+{
+    constexpr int D = 128;
+    constexpr int RBW = 32 / G;       // query rows per wavefront (32 columns = rows x heads of the group)
+    constexpr int RBG = 4 * RBW;      // query rows per workgroup
+    constexpr int PITCH = 256;        // bytes per position row of the K and V tiles in LDS
+    constexpr int TILE = 32 * PITCH;  // one tile: 32 positions
+    constexpr int NB = 4;             // (K, V) tile pairs: one is multiplied while three are on their way
+    __shared__ __attribute__((aligned(1024))) unsigned char tiles[NB * 2 * TILE];
+    __shared__ __attribute__((aligned(16))) unsigned char ok_bytes[NB][4];      // validity of the 32 positions of a pair: bit idx % 8 of byte idx / 8
+    __shared__ unsigned long long run_mask[4];
 
     const int t0 = (int)blockIdx.x / a.Hkv, hk = (int)blockIdx.x % a.Hkv;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int wu = __builtin_amdgcn_readfirstlane(w);
     const int sq = a.seq[t0], p0 = a.pos[t0];
     const bool row_ok = sq >= 0 && sq < a.n_seqs && p0 >= 0;
-    // does this row lead a block?  (the row before it is the same sequence's previous position, and the
-    // position is not a multiple of the block: then an earlier row leads)
-    if (row_ok && t0 > 0 && (p0 % RB) != 0 && a.seq[t0 - 1] == sq && a.pos[t0 - 1] == p0 - 1) return;
-    // rows of the block: up to the next multiple of RB, as long as the run continues
+    // does this row lead a block?  (no, if the row before it is the same sequence's previous position and
+    // the position is not a multiple of the block: then an earlier row leads)
+    if (row_ok && t0 > 0 && (p0 % RBG) != 0 && a.seq[t0 - 1] == sq && a.pos[t0 - 1] == p0 - 1) return;
+    // rows of the block: up to the next multiple of RBG, as long as the run continues
     int nrows = 1;
     if (row_ok) {
-        const int limit = RB - (p0 % RB);
-        bool cont = false;
-        if (lane > 0 && lane < limit && t0 + lane < a.T) cont = a.seq[t0 + lane] == sq && a.pos[t0 + lane] == p0 + lane;
-        const unsigned long long mask = __builtin_amdgcn_ballot_w64(cont) | 1ull;
-        nrows = __builtin_ctzll(~mask);
+        const int limit = RBG - (p0 % RBG);
+        bool cont = tid == 0;
+        if (tid > 0 && tid < limit && t0 + tid < a.T) cont = a.seq[t0 + tid] == sq && a.pos[t0 + tid] == p0 + tid;
+        const unsigned long long mk = __builtin_amdgcn_ballot_w64(cont);
+        if (lane == 0) run_mask[w] = mk;
+        __syncthreads();
+        nrows = 0;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) {
+            const unsigned long long mw = run_mask[ww];
+            if (nrows == 64 * ww) nrows += mw == ~0ull ? 64 : __builtin_ctzll(~mw);
+        }
+        nrows = __builtin_amdgcn_readfirstlane(nrows);
     }
     const long long cap = (long long)a.max_blocks * a.bs;
     int n_ctx = 0;
     if (row_ok) n_ctx = (int)((long long)p0 + nrows < cap ? (long long)p0 + nrows : cap);
+    const int n_chunks = (n_ctx + 31) >> 5;
     const int32_t *bt = a.bt + (size_t)(row_ok ? sq : 0) * a.max_blocks;
     const int Nkv = a.Hkv * D;
     const long long n_blocks = a.n_slots / a.bs;
 
-    // this lane's column: query row r_j of the block, query head g_j of the group
-    const int r_j = li / G, g_j = li % G;
+    // this lane's column: query row r_j of the block (rows w*RBW .. of this wavefront), query head g_j
+    const int r_j = w * RBW + li / G, g_j = li % G;
     const bool col_ok = row_ok && r_j < nrows;
-    const int lim_j = col_ok ? p0 + r_j : -1;   // last position the column attends to
+    const int lim_j = col_ok ? p0 + r_j : -1;                        // last position the column attends to
+    const int lim_w = (row_ok && wu * RBW < nrows) ? p0 + min((wu + 1) * RBW, nrows) - 1 : -1;   // ... and any column of this wavefront
+    const int lim_first = p0 + wu * RBW;                             // ... and the wavefront's first column
     const size_t q_at = ((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * D;
     bf16x8 qf[8];
 #pragma unroll
@@ -89,6 +142,10 @@ __global__ __launch_bounds__(256) void paged_attention_blocks_kernel(AttnArgs a)
         if (col_ok) v = *(const u32x4 *)((const bf16_t *)a.q + q_at + 16 * s + 8 * lh);
         qf[s] = __builtin_bit_cast(bf16x8, v);
     }
+    // (a use of the query registers ahead of the loop: the compiler places its wait for these loads here and
+    // not in front of the first MFMA of every step, where it would also wait for the copies in flight)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
 
     f32x16 acc[4];
 #pragma unroll
@@ -97,70 +154,120 @@ __global__ __launch_bounds__(256) void paged_attention_blocks_kernel(AttnArgs a)
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
     float m = AB_M_FLOOR, l = 0.f;
 
-    // V tile addressing.  Write: the row of position i (this lane's) with position bits 2 and 3 exchanged;
-    // 16-byte chunks XOR-swizzled by 4 * (row % 4).  Read: fragment of d tile `t`, k step `ks`.
-    lds_byte *const tile = (lds_byte *)vt[w];
-    const int vrow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
+    // ---- copies global -> LDS: wavefront w fills positions 8w .. 8w+7 of a block of 32 with two K and two V
+    // instructions; instruction ii covers positions 8w + 4ii .. +3 (one cache block: block sizes are multiples
+    // of 4, so its table entry is a scalar), lane -> position + lane / 16, physical 16-byte chunk lane % 16.
+    // K tile: row = position, the physical chunk holds logical chunk XOR (row % 16) (the score product reads
+    // one logical chunk of 32 rows).  V tile: row = position, XOR 4 * (row % 4) (transposing read).
+    const int lr = lane >> 4, lq = lane & 15;
+    const uint32_t tiles_at = (uint32_t)(uintptr_t)(lds_byte *)tiles;
+    // Table entries are read with scalar loads written as assembly (the table index of four aligned positions
+    // is the same in every lane); the index is clamped into the table row, an entry past the context reads as -1.
+    auto entry_at = [&](int cb, int ii) {   // byte offset of the table entry of positions cb + 8w + 4ii .. +3
+        const int pu = cb + 8 * wu + 4 * ii;
+        const int e = a.bs_shift >= 0 ? (pu >> a.bs_shift) : (pu / a.bs);
+        return 4 * min(e, a.max_blocks - 1);
+    };
+    auto entry_or_none = [&](int cb, int ii, int e) { return cb + 8 * wu + 4 * ii < n_ctx ? e : -1; };
+    auto lookup_pair = [&](int cb, int &b0, int &b1) {
+        int e0, e1;
+        asm volatile("s_load_dword %0, %2, %3\n\ts_load_dword %1, %2, %4\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(e0), "=&s"(e1)
+                     : "s"(bt), "s"(entry_at(cb, 0)), "s"(entry_at(cb, 1))
+                     : "memory");
+        b0 = entry_or_none(cb, 0, e0);
+        b1 = entry_or_none(cb, 1, e1);
+    };
+    // One step's synchronisation: this wavefront's LDS writes are done, the table entries of block cb are
+    // requested, all copies but the eight newest have landed, the barrier, the entries have arrived.
+    auto step_sync = [&](int cb, int &b0, int &b1) {
+        int e0, e1;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_load_dword %0, %2, %3\n\ts_load_dword %1, %2, %4\n\t"
+                     "s_waitcnt vmcnt(8)\n\ts_barrier\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(e0), "=&s"(e1)
+                     : "s"(bt), "s"(entry_at(cb, 0)), "s"(entry_at(cb, 1))
+                     : "memory");
+        b0 = entry_or_none(cb, 0, e0);
+        b1 = entry_or_none(cb, 1, e1);
+    };
+    auto issue = [&](int c, int blk0, int blk1) {
+        const int cb = 32 * c;
+        const uint32_t pair_at = tiles_at + (uint32_t)(c & (NB - 1)) * (2 * TILE);
+        unsigned okb = 0;
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii) {
+            const int blk = ii ? blk1 : blk0;
+            const int pu = cb + 8 * wu + 4 * ii;                    // first of the four positions
+            const bool blk_ok = blk >= 0 && blk < n_blocks;
+            const int n_ok = blk_ok ? max(0, min(4, n_ctx - pu)) : 0;
+            okb |= ((1u << n_ok) - 1u) << (4 * ii);
+            const int row = 8 * wu + 4 * ii + lr;
+            const bool have = lr < n_ok;
+            const int off = a.bs_shift >= 0 ? (pu & (a.bs - 1)) : (pu % a.bs);
+            const size_t at = ((size_t)(blk_ok ? blk : 0) * a.bs + off + lr) * Nkv + (size_t)hk * D;
+            const int kch = lq ^ (row & 15), vch = lq ^ ((row & 3) << 2);
+            const void *kp = have ? (const void *)((const bf16_t *)a.kc + at + 8 * kch) : (const void *)ab_zero_chunk;
+            const void *vp = have ? (const void *)((const bf16_t *)a.vc + at + 8 * vch) : (const void *)ab_zero_chunk;
+            load_lds16(pair_at + (uint32_t)(8 * wu + 4 * ii) * PITCH, kp);
+            load_lds16(pair_at + TILE + (uint32_t)(8 * wu + 4 * ii) * PITCH, vp);
+        }
+        if (lane == 0) ok_bytes[c & (NB - 1)][wu] = (unsigned char)okb;
+    };
+
+    // K fragment of k step s: row li, chunk 2s + lh
+    uint32_t k_r[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) k_r[s] = li * PITCH + (((2 * s + lh) ^ (li & 15)) << 4);
+    // V fragment of d tile t: the transposing read hands a lane k = 4lh .. 4lh+3 of its 16 (first read) and
+    // 8 + 4lh .. (second read, eight rows further on): the positions its score registers hold
     uint32_t vaddr[4];
     {
         const int s16 = lane & 15, j = s16 >> 2, blk = (lane >> 4) & 1;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int chunk = 4 * t + 2 * blk + ((s16 & 3) >> 1);
-            vaddr[t] = (uint32_t)(8 * lh + j) * VPITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s16 & 1) << 3);
+            vaddr[t] = (uint32_t)(4 * lh + j) * PITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s16 & 1) << 3);
         }
     }
 
-    for (int cb = 32 * w; cb < n_ctx; cb += 128) {
-        // ---- this lane's position: its K row into the A operand, its V row into LDS -------------
-        const int pi = cb + li;
-        bool have = pi < n_ctx;
-        long long slot = 0;
-        if (have) {
-            const int bi = a.bs_shift >= 0 ? (pi >> a.bs_shift) : (pi / a.bs);
-            const int blk = bt[bi];
-            have = blk >= 0 && blk < n_blocks;
-            slot = (long long)blk * a.bs + (pi - bi * a.bs);
-        }
-        const unsigned okmask = (unsigned)__builtin_amdgcn_ballot_w64(have);   // bits 0..31: positions of the block
-        const size_t at = (size_t)slot * Nkv + (size_t)hk * D + 8 * lh;
-        u32x4 kf[8], vf[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            kf[s] = u32x4{0u, 0u, 0u, 0u};
-            vf[s] = kf[s];
-            if (have) {
-                kf[s] = *(const u32x4 *)((const bf16_t *)a.kc + at + 16 * s);
-                vf[s] = *(const u32x4 *)((const bf16_t *)a.vc + at + 16 * s);
-            }
-        }
+    auto consume = [&](int c) {
+        const int cb = 32 * c;
+        const lds_byte *kb = (const lds_byte *)tiles + (c & (NB - 1)) * (2 * TILE), *vb = kb + TILE;
         // ---- scores^T = K . Q^T ------------------------------------------------------------------
         f32x16 sc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) sc[e] = 0.f;
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[s], sc, 0, 0, 0);
-#pragma unroll
-        for (int s = 0; s < 8; ++s)
-            *(__attribute__((address_space(3))) u32x4 *)(tile + vrow * VPITCH + (((2 * s + lh) ^ ((vrow & 3) << 2)) << 4)) = vf[s];
-        // ---- softmax down this lane's column -----------------------------------------------------
-        float mx = AB_NEG_INF;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int idx = 8 * (v >> 2) + 4 * lh + (v & 3);
-            const bool on = ((okmask >> idx) & 1u) && cb + idx <= lim_j;
-            sc[v] = on ? sc[v] * a.scale_log2e : AB_NEG_INF;
-            mx = fmaxf(mx, sc[v]);
+        for (int s = 0; s < 8; ++s) {
+            const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8 *)(kb + k_r[s]);
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sc, 0, 0, 0);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float mn = fmaxf(m, mx);
+        bf16x8 vf[2][4];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) vf[ks][t] = read_tr_frag(vb + vaddr[t] + ks * 16 * PITCH, PITCH);
+        // ---- softmax down this lane's column -----------------------------------------------------
+        const unsigned okmask = __builtin_amdgcn_readfirstlane(*(const unsigned *)ok_bytes[c & (NB - 1)]);
+        if (!(okmask == 0xffffffffu && cb + 31 <= lim_first)) {   // a block that every column of the wavefront sees whole needs no mask
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int idx = 8 * (v >> 2) + 4 * lh + (v & 3);
+                const bool on = ((okmask >> idx) & 1u) && cb + idx <= lim_j;
+                sc[v] = on ? sc[v] : AB_NEG_INF;
+            }
+        }
+        float mx = max3(sc[0], sc[1], sc[2]);
+#pragma unroll
+        for (int v = 3; v < 15; v += 2) mx = max3(mx, sc[v], sc[v + 1]);
+        mx = max_with_other_half(fmaxf(mx, sc[15]));
+        const float mn = fmaxf(m, mx * a.scale_log2e);
         const float corr = __builtin_amdgcn_exp2f(m - mn);
         m = mn;
         float ps = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            sc[v] = __builtin_amdgcn_exp2f(sc[v] - mn);
+            sc[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[v], a.scale_log2e, -mn));
             ps += sc[v];
         }
         l = l * corr + ps;
@@ -171,57 +278,47 @@ __global__ __launch_bounds__(256) void paged_attention_blocks_kernel(AttnArgs a)
                 for (int e = 0; e < 16; ++e) acc[t][e] *= corr;
         }
         // ---- out^T += V^T . P : P straight from the score registers --------------------------------
-        bf16x8 pf[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const u32x4 pv = {pack_bf16(sc[8 * ks + 0], sc[8 * ks + 1]), pack_bf16(sc[8 * ks + 2], sc[8 * ks + 3]),
                               pack_bf16(sc[8 * ks + 4], sc[8 * ks + 5]), pack_bf16(sc[8 * ks + 6], sc[8 * ks + 7])};
-            pf[ks] = __builtin_bit_cast(bf16x8, pv);
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks][t], pf, acc[t], 0, 0, 0);
         }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr_frag(tile + vaddr[t] + ks * 16 * VPITCH, VPITCH), pf[ks],
-                                                                 acc[t], 0, 0, 0);
+    };
+
+    // ---- the context, 32 positions at a time: all four wavefronts share the tiles -------------------
+    // Block c lives in tile pair c % 4.  In the step of block c every wavefront waits for its own copies of
+    // block c (those of c+1 and c+2, four instructions each, stay in flight), the barrier makes that hold for
+    // all of them and tells that block c-1 has been multiplied by everyone; its pair then takes the copies of
+    // block c+3, whose table entries were read a step earlier (those of block c+4 are read across the barrier).  Blocks past the context are copied too (all
+    // zeros, from one 16-byte constant), which keeps the count of copies in flight the same in every step.
+    {
+        int b0, b1, n0, n1;
+        lookup_pair(0, b0, b1);
+        issue(0, b0, b1);
+        lookup_pair(32, b0, b1);
+        issue(1, b0, b1);
+        lookup_pair(64, b0, b1);
+        issue(2, b0, b1);
+        lookup_pair(96, b0, b1);
+        for (int c = 0; c < n_chunks; ++c) {
+            step_sync(32 * (c + 4), n0, n1);
+            issue(c + 3, b0, b1);
+            b0 = n0, b1 = n1;
+            if (32 * c <= lim_w) consume(c);
+        }
+        // nothing may be on its way into LDS when the workgroup gives it back
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
-    // ---- the two lanes of a column add their weight sums; wavefronts 1..3 hand over to wavefront 0 ---
-    l += __shfl_xor(l, 32);
-    if (w > 0) {
-        float *dst = mrg[w - 1][lane];
-        dst[0] = m;
-        dst[1] = l;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) dst[2 + 16 * t + e] = acc[t][e];
-    }
-    __syncthreads();
-    if (w > 0) return;
-    float M = m;
-#pragma unroll
-    for (int ww = 0; ww < 3; ++ww) M = fmaxf(M, mrg[ww][lane][0]);
-    float f0 = __builtin_amdgcn_exp2f(m - M);
-    float L = l * f0;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] *= f0;
-#pragma unroll
-    for (int ww = 0; ww < 3; ++ww) {
-        const float *src = mrg[ww][lane];
-        const float f = __builtin_amdgcn_exp2f(src[0] - M);
-        L += src[1] * f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[t][e] += src[2 + 16 * t + e] * f;
-    }
+    // ---- the two lanes of a column add their weight sums; normalise and store ----------------------
+    l = sum_with_other_half(l);
     // a row that is not valid leads a block of its own and gets zeros
-    if (!(col_ok || (!row_ok && r_j == 0))) return;
-    const float inv = L > 0.f ? 1.f / L : 0.f;
-    bf16_t *orow = (bf16_t *)a.out + ((size_t)(t0 + r_j) * a.Hq + (size_t)hk * G + g_j) * D;
+    if (!(col_ok || (!row_ok && w == 0 && li < G))) return;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    bf16_t *orow = (bf16_t *)a.out + ((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * D;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
