@@ -83,7 +83,7 @@ __device__ __forceinline__ float sum_with_other_half(float x)
 __device__ const uint32_t ab_zero_chunk[4] = {0u, 0u, 0u, 0u};
 
 template <int G>
-__global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs a)
+__global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs a, int R)
 {
     constexpr int D = 128;
     constexpr int RBW = 32 / G;       // query rows per wavefront (32 columns = rows x heads of the group)
@@ -95,14 +95,58 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     __shared__ __attribute__((aligned(16))) unsigned char ok_bytes[NB][4];      // validity of the 32 positions of a pair: bit idx % 8 of byte idx / 8
     __shared__ unsigned long long run_mask[4];
 
-    const int t0 = (int)blockIdx.x / a.Hkv, hk = (int)blockIdx.x % a.Hkv;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
     const int wu = __builtin_amdgcn_readfirstlane(w);
+    const int hk = (int)blockIdx.x % a.Hkv;
+    // ---- this workgroup's R batch rows (R a power of two <= 32, <= RBG) ------------------------------------
+    // With R < RBG a long run of rows has a leading row in every (RBG / R)-th range only, and workgroups are
+    // handed to the shader engines of an XCD in turn (four of them): without the exchange of the two low index
+    // bits below, all the work of such a batch would land on one engine in four.
+    int k = (int)blockIdx.x / a.Hkv;
+    {
+        const int n_ranges = (a.T + R - 1) / R, mm = RBG / R;
+        if (mm > 1 && (k | 3) < n_ranges) k ^= (k / mm) & (mm >= 4 ? 3 : 1);
+    }
+    const int r_begin = k * R, r_end = min(a.T, r_begin + R);
+    // which of them lead a block: a row does unless the row before it in the batch is the same sequence's
+    // previous position and the position is not a multiple of RBG (then an earlier row leads)
+    unsigned leaders;
+    {
+        bool lead = false;
+        const int t = r_begin + lane;
+        if (lane < R && t < r_end) {
+            const int sq = a.seq[t], p0 = a.pos[t];
+            const bool ok = sq >= 0 && sq < a.n_seqs && p0 >= 0;
+            lead = !(ok && t > 0 && (p0 % RBG) != 0 && a.seq[t - 1] == sq && a.pos[t - 1] == p0 - 1);
+        }
+        leaders = (unsigned)__builtin_amdgcn_ballot_w64(lead);
+    }
+    const int Nkv = a.Hkv * D;
+    const long long n_blocks = a.n_slots / a.bs;
+    const long long cap = (long long)a.max_blocks * a.bs;
+    const int lr = lane >> 4, lq = lane & 15;
+    const uint32_t tiles_at = (uint32_t)(uintptr_t)(lds_byte *)tiles;
+    // K fragment of k step s: row li, chunk 2s + lh
+    uint32_t k_r[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) k_r[s] = li * PITCH + (((2 * s + lh) ^ (li & 15)) << 4);
+    // V fragment of d tile t: the transposing read hands a lane k = 4lh .. 4lh+3 of its 16 (first read) and
+    // 8 + 4lh .. (second read, eight rows further on): the positions its score registers hold
+    uint32_t vaddr[4];
+    {
+        const int s16 = lane & 15, j = s16 >> 2, blk = (lane >> 4) & 1;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int chunk = 4 * t + 2 * blk + ((s16 & 3) >> 1);
+            vaddr[t] = (uint32_t)(4 * lh + j) * PITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s16 & 1) << 3);
+        }
+    }
+
+  for (bool first = true; leaders; leaders &= leaders - 1, first = false) {
+    const int t0 = r_begin + __builtin_ctz(leaders);
+    if (!first) __syncthreads();      // everyone is done with the tiles and masks of the block before
     const int sq = a.seq[t0], p0 = a.pos[t0];
     const bool row_ok = sq >= 0 && sq < a.n_seqs && p0 >= 0;
-    // does this row lead a block?  (no, if the row before it is the same sequence's previous position and
-    // the position is not a multiple of the block: then an earlier row leads)
-    if (row_ok && t0 > 0 && (p0 % RBG) != 0 && a.seq[t0 - 1] == sq && a.pos[t0 - 1] == p0 - 1) return;
     // rows of the block: up to the next multiple of RBG, as long as the run continues
     int nrows = 1;
     if (row_ok) {
@@ -120,13 +164,10 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
         }
         nrows = __builtin_amdgcn_readfirstlane(nrows);
     }
-    const long long cap = (long long)a.max_blocks * a.bs;
     int n_ctx = 0;
     if (row_ok) n_ctx = (int)((long long)p0 + nrows < cap ? (long long)p0 + nrows : cap);
     const int n_chunks = (n_ctx + 31) >> 5;
     const int32_t *bt = a.bt + (size_t)(row_ok ? sq : 0) * a.max_blocks;
-    const int Nkv = a.Hkv * D;
-    const long long n_blocks = a.n_slots / a.bs;
 
     // this lane's column: query row r_j of the block (rows w*RBW .. of this wavefront), query head g_j
     const int r_j = w * RBW + li / G, g_j = li % G;
@@ -159,8 +200,6 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     // of 4, so its table entry is a scalar), lane -> position + lane / 16, physical 16-byte chunk lane % 16.
     // K tile: row = position, the physical chunk holds logical chunk XOR (row % 16) (the score product reads
     // one logical chunk of 32 rows).  V tile: row = position, XOR 4 * (row % 4) (transposing read).
-    const int lr = lane >> 4, lq = lane & 15;
-    const uint32_t tiles_at = (uint32_t)(uintptr_t)(lds_byte *)tiles;
     // Table entries are read with scalar loads written as assembly (the table index of four aligned positions
     // is the same in every lane); the index is clamped into the table row, an entry past the context reads as -1.
     auto entry_at = [&](int cb, int ii) {   // byte offset of the table entry of positions cb + 8w + 4ii .. +3
@@ -213,22 +252,6 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
         }
         if (lane == 0) ok_bytes[c & (NB - 1)][wu] = (unsigned char)okb;
     };
-
-    // K fragment of k step s: row li, chunk 2s + lh
-    uint32_t k_r[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) k_r[s] = li * PITCH + (((2 * s + lh) ^ (li & 15)) << 4);
-    // V fragment of d tile t: the transposing read hands a lane k = 4lh .. 4lh+3 of its 16 (first read) and
-    // 8 + 4lh .. (second read, eight rows further on): the positions its score registers hold
-    uint32_t vaddr[4];
-    {
-        const int s16 = lane & 15, j = s16 >> 2, blk = (lane >> 4) & 1;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int chunk = 4 * t + 2 * blk + ((s16 & 3) >> 1);
-            vaddr[t] = (uint32_t)(4 * lh + j) * PITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s16 & 1) << 3);
-        }
-    }
 
     auto consume = [&](int c) {
         const int cb = 32 * c;
@@ -316,27 +339,33 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     // ---- the two lanes of a column add their weight sums; normalise and store ----------------------
     l = sum_with_other_half(l);
     // a row that is not valid leads a block of its own and gets zeros
-    if (!(col_ok || (!row_ok && w == 0 && li < G))) return;
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-    bf16_t *orow = (bf16_t *)a.out + ((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * D;
+    if (col_ok || (!row_ok && w == 0 && li < G)) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        bf16_t *orow = (bf16_t *)a.out + ((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * D;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const u32x2 o = {pack_bf16(acc[t][4 * b + 0] * inv, acc[t][4 * b + 1] * inv),
-                             pack_bf16(acc[t][4 * b + 2] * inv, acc[t][4 * b + 3] * inv)};
-            *(u32x2 *)(orow + 32 * t + 8 * b + 4 * lh) = o;
-        }
+            for (int b = 0; b < 4; ++b) {
+                const u32x2 o = {pack_bf16(acc[t][4 * b + 0] * inv, acc[t][4 * b + 1] * inv),
+                                 pack_bf16(acc[t][4 * b + 2] * inv, acc[t][4 * b + 3] * inv)};
+                *(u32x2 *)(orow + 32 * t + 8 * b + 4 * lh) = o;
+            }
+    }
+  }
 }
 
 int launch_attention_blocks(const AttnArgs &a, int G, hipStream_t stream)
 {
-    const dim3 grid((unsigned)a.T * (unsigned)a.Hkv), block(256);
+    // batch rows per workgroup: a whole row block where that still makes a few workgroups per CU, fewer for
+    // small batches (a decode batch: every row leads a block of its own)
+    int R = 32 / G * 4 < 32 ? 32 / G * 4 : 32;
+    while (R > 1 && (long long)((a.T + R - 1) / R) * a.Hkv < 512) R /= 2;
+    const dim3 grid((unsigned)((a.T + R - 1) / R) * (unsigned)a.Hkv), block(256);
     switch (G) {
-    case 1: hipLaunchKernelGGL(paged_attention_blocks_kernel<1>, grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL(paged_attention_blocks_kernel<2>, grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL(paged_attention_blocks_kernel<4>, grid, block, 0, stream, a); break;
-    case 8: hipLaunchKernelGGL(paged_attention_blocks_kernel<8>, grid, block, 0, stream, a); break;
+    case 1: hipLaunchKernelGGL(paged_attention_blocks_kernel<1>, grid, block, 0, stream, a, R); break;
+    case 2: hipLaunchKernelGGL(paged_attention_blocks_kernel<2>, grid, block, 0, stream, a, R); break;
+    case 4: hipLaunchKernelGGL(paged_attention_blocks_kernel<4>, grid, block, 0, stream, a, R); break;
+    case 8: hipLaunchKernelGGL(paged_attention_blocks_kernel<8>, grid, block, 0, stream, a, R); break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();
