@@ -53,18 +53,22 @@ __device__ __forceinline__ void load_lds16(uint32_t lds_addr, const void *p)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(p) : "memory");
 }
-__device__ __forceinline__ float max3(float x, float y, float z)
+// the same with a scalar base address and a 32-bit byte offset per lane
+__device__ __forceinline__ void load_lds16(uint32_t lds_addr, const void *base, uint32_t voffset)
 {
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
-    return r;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voffset), "s"(base) : "memory");
 }
+// (plain fmaxf, which the compiler fuses into v_max3_f32: an assembly statement that reads the registers
+// an MFMA has just written would miss the wait states the compiler places for instructions it knows)
+__device__ __forceinline__ float max3(float x, float y, float z) { return fmaxf(fmaxf(x, y), z); }
 // lo <- the value the lower 32 lanes hold in x, hi <- the upper 32 lanes' (each in all 64 lanes): one
 // v_permlane32_swap on two copies of x.  Assembly: the builtin of this name returned the first result twice.
 __device__ __forceinline__ void both_halves(float x, float &lo, float &hi)
 {
     lo = x, hi = x;
-    asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+    // (wait states on both sides: the compiler does not see the instruction, so it cannot place the ones
+    // that a VALU write before it and a VALU read after it need)
+    asm("s_nop 3\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 3" : "+v"(lo), "+v"(hi));
 }
 __device__ __forceinline__ float max_with_other_half(float x)
 {
@@ -94,6 +98,8 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     __shared__ __attribute__((aligned(1024))) unsigned char tiles[NB * 2 * TILE];
     __shared__ __attribute__((aligned(16))) unsigned char ok_bytes[NB][4];      // validity of the 32 positions of a pair: bit idx % 8 of byte idx / 8
     __shared__ unsigned long long run_mask[4];
+    constexpr int WIN = 64;            // blocks of 32 positions whose table entries the window below holds
+    __shared__ int32_t window[WIN * 32 / 4 + 2];   // block sizes are multiples of 4
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
     const int wu = __builtin_amdgcn_readfirstlane(w);
@@ -126,6 +132,10 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     const long long cap = (long long)a.max_blocks * a.bs;
     const int lr = lane >> 4, lq = lane & 15;
     const uint32_t tiles_at = (uint32_t)(uintptr_t)(lds_byte *)tiles;
+    // byte offsets of a lane's 16 bytes from the first of its instruction's four cache rows (ii = 0, 1; V: both)
+    const uint32_t row_off = (uint32_t)lr * (uint32_t)Nkv * 2u;
+    const uint32_t k_off0 = row_off + (uint32_t)((lq ^ ((8 * wu + lr) & 15)) << 4), k_off1 = row_off + (uint32_t)((lq ^ ((8 * wu + 4 + lr) & 15)) << 4);
+    const uint32_t v_off = row_off + (uint32_t)((lq ^ (lr << 2)) << 4);
     // K fragment of k step s: row li, chunk 2s + lh
     uint32_t k_r[8];
 #pragma unroll
@@ -200,34 +210,21 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     // of 4, so its table entry is a scalar), lane -> position + lane / 16, physical 16-byte chunk lane % 16.
     // K tile: row = position, the physical chunk holds logical chunk XOR (row % 16) (the score product reads
     // one logical chunk of 32 rows).  V tile: row = position, XOR 4 * (row % 4) (transposing read).
-    // Table entries are read with scalar loads written as assembly (the table index of four aligned positions
-    // is the same in every lane); the index is clamped into the table row, an entry past the context reads as -1.
-    auto entry_at = [&](int cb, int ii) {   // byte offset of the table entry of positions cb + 8w + 4ii .. +3
+    // Table entries come from a window in LDS that holds those of WIN blocks of 32 positions and is refilled
+    // by the whole workgroup when the lookups reach its end (the index of four aligned positions is the same
+    // in every lane); an entry past the context reads as -1.
+    auto entry_of = [&](int pu) { return a.bs_shift >= 0 ? (pu >> a.bs_shift) : (pu / a.bs); };
+    int win_first = 0;                       // table index of window[0]
+    auto refill = [&](int cw) {              // entries of blocks cw .. cw + WIN - 1; all wavefronts call it together
+        win_first = entry_of(32 * cw);
+        const int last = entry_of(min(32 * (cw + WIN), n_ctx) - 1);      // n_ctx > 32 * cw whenever this is called
+        __syncthreads();
+        for (int i = tid; win_first + i <= last; i += 256) window[i] = bt[win_first + i];
+        __syncthreads();
+    };
+    auto lookup = [&](int cb, int ii) {
         const int pu = cb + 8 * wu + 4 * ii;
-        const int e = a.bs_shift >= 0 ? (pu >> a.bs_shift) : (pu / a.bs);
-        return 4 * min(e, a.max_blocks - 1);
-    };
-    auto entry_or_none = [&](int cb, int ii, int e) { return cb + 8 * wu + 4 * ii < n_ctx ? e : -1; };
-    auto lookup_pair = [&](int cb, int &b0, int &b1) {
-        int e0, e1;
-        asm volatile("s_load_dword %0, %2, %3\n\ts_load_dword %1, %2, %4\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&s"(e0), "=&s"(e1)
-                     : "s"(bt), "s"(entry_at(cb, 0)), "s"(entry_at(cb, 1))
-                     : "memory");
-        b0 = entry_or_none(cb, 0, e0);
-        b1 = entry_or_none(cb, 1, e1);
-    };
-    // One step's synchronisation: this wavefront's LDS writes are done, the table entries of block cb are
-    // requested, all copies but the eight newest have landed, the barrier, the entries have arrived.
-    auto step_sync = [&](int cb, int &b0, int &b1) {
-        int e0, e1;
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_load_dword %0, %2, %3\n\ts_load_dword %1, %2, %4\n\t"
-                     "s_waitcnt vmcnt(8)\n\ts_barrier\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&s"(e0), "=&s"(e1)
-                     : "s"(bt), "s"(entry_at(cb, 0)), "s"(entry_at(cb, 1))
-                     : "memory");
-        b0 = entry_or_none(cb, 0, e0);
-        b1 = entry_or_none(cb, 1, e1);
+        return pu < n_ctx ? __builtin_amdgcn_readfirstlane(window[entry_of(pu) - win_first]) : -1;
     };
     auto issue = [&](int c, int blk0, int blk1) {
         const int cb = 32 * c;
@@ -240,15 +237,19 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
             const bool blk_ok = blk >= 0 && blk < n_blocks;
             const int n_ok = blk_ok ? max(0, min(4, n_ctx - pu)) : 0;
             okb |= ((1u << n_ok) - 1u) << (4 * ii);
-            const int row = 8 * wu + 4 * ii + lr;
-            const bool have = lr < n_ok;
             const int off = a.bs_shift >= 0 ? (pu & (a.bs - 1)) : (pu % a.bs);
-            const size_t at = ((size_t)(blk_ok ? blk : 0) * a.bs + off + lr) * Nkv + (size_t)hk * D;
-            const int kch = lq ^ (row & 15), vch = lq ^ ((row & 3) << 2);
-            const void *kp = have ? (const void *)((const bf16_t *)a.kc + at + 8 * kch) : (const void *)ab_zero_chunk;
-            const void *vp = have ? (const void *)((const bf16_t *)a.vc + at + 8 * vch) : (const void *)ab_zero_chunk;
-            load_lds16(pair_at + (uint32_t)(8 * wu + 4 * ii) * PITCH, kp);
-            load_lds16(pair_at + TILE + (uint32_t)(8 * wu + 4 * ii) * PITCH, vp);
+            const size_t at = ((size_t)(blk_ok ? blk : 0) * a.bs + off) * Nkv + (size_t)hk * D;   // first of the four cache rows
+            const uint32_t k_to = pair_at + (uint32_t)(8 * wu + 4 * ii) * PITCH, v_to = k_to + TILE;
+            if (n_ok == 4) {   // the usual case: scalar base, the lane's constant offset
+                load_lds16(k_to, (const bf16_t *)a.kc + at, ii ? k_off1 : k_off0);
+                load_lds16(v_to, (const bf16_t *)a.vc + at, v_off);
+            } else {           // rows that are not part of the context read 16 zero bytes
+                const bool have = lr < n_ok;
+                const void *kp = have ? (const void *)((const char *)((const bf16_t *)a.kc + at) + (ii ? k_off1 : k_off0)) : (const void *)ab_zero_chunk;
+                const void *vp = have ? (const void *)((const char *)((const bf16_t *)a.vc + at) + v_off) : (const void *)ab_zero_chunk;
+                load_lds16(k_to, kp);
+                load_lds16(v_to, vp);
+            }
         }
         if (lane == 0) ok_bytes[c & (NB - 1)][wu] = (unsigned char)okb;
     };
@@ -315,23 +316,30 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     // Block c lives in tile pair c % 4.  In the step of block c every wavefront waits for its own copies of
     // block c (those of c+1 and c+2, four instructions each, stay in flight), the barrier makes that hold for
     // all of them and tells that block c-1 has been multiplied by everyone; its pair then takes the copies of
-    // block c+3, whose table entries were read a step earlier (those of block c+4 are read across the barrier).  Blocks past the context are copied too (all
+    // block c+3, whose table entries were looked up a step earlier.  Blocks past the context are copied too (all
     // zeros, from one 16-byte constant), which keeps the count of copies in flight the same in every step.
     {
-        int b0, b1, n0, n1;
-        lookup_pair(0, b0, b1);
-        issue(0, b0, b1);
-        lookup_pair(32, b0, b1);
-        issue(1, b0, b1);
-        lookup_pair(64, b0, b1);
-        issue(2, b0, b1);
-        lookup_pair(96, b0, b1);
-        for (int c = 0; c < n_chunks; ++c) {
-            step_sync(32 * (c + 4), n0, n1);
-            issue(c + 3, b0, b1);
-            b0 = n0, b1 = n1;
-            if (32 * c <= lim_w) consume(c);
+        if (n_chunks > 0) refill(0);
+#pragma unroll
+        for (int k = 0; k < NB - 1; ++k) issue(k, lookup(32 * k, 0), lookup(32 * k, 1));
+        int b0 = lookup(32 * (NB - 1), 0), b1 = lookup(32 * (NB - 1), 1);
+        auto step = [&](int c) {
+            // this wavefront's copies of block c have landed (eight newer ones may be in flight); behind the
+            // barrier that holds for every wavefront, and all of them are done with block c-1
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            issue(c + NB - 1, b0, b1);
+            const int cn = c + NB;
+            if ((cn & (WIN - 1)) == 0 && 32 * cn < n_ctx) refill(cn);
+            b0 = lookup(32 * cn, 0), b1 = lookup(32 * cn, 1);
+        };
+        // (two loops: the accumulators live in the first only)
+        const int n_chunks_w = lim_w >= 0 ? (lim_w >> 5) + 1 : 0;
+        int c = 0;
+        for (; c < n_chunks_w; ++c) {
+            step(c);
+            consume(c);
         }
+        for (; c < n_chunks; ++c) step(c);
         // nothing may be on its way into LDS when the workgroup gives it back
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
@@ -359,7 +367,7 @@ int launch_attention_blocks(const AttnArgs &a, int G, hipStream_t stream)
     // batch rows per workgroup: a whole row block where that still makes a few workgroups per CU, fewer for
     // small batches (a decode batch: every row leads a block of its own)
     int R = 32 / G * 4 < 32 ? 32 / G * 4 : 32;
-    while (R > 1 && (long long)((a.T + R - 1) / R) * a.Hkv < 512) R /= 2;
+    while (R > 1 && (long long)((a.T + R - 1) / R) * a.Hkv < 2048) R /= 2;
     const dim3 grid((unsigned)((a.T + R - 1) / R) * (unsigned)a.Hkv), block(256);
     switch (G) {
     case 1: hipLaunchKernelGGL(paged_attention_blocks_kernel<1>, grid, block, 0, stream, a, R); break;

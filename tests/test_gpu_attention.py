@@ -270,6 +270,17 @@ def test_suffix_call_on_a_decode_batch_and_on_interleaved_rows():
     assert maxnorm_rel(out2, d2.oracle()) <= TOL["bf16"]
 
 
+def test_suffix_call_gives_the_same_bits_on_every_call():
+    """The row-block kernel takes no timing-dependent decision: 200 calls on one batch (blocks that need no
+    mask, diagonal blocks, single rows), every one bit-identical to the first."""
+    c = wl.attention_case("suffix-repeat", "bf16", [200, 90, 700], [40, 1, 65], 8, 2, 128, 16, seed=wl.SEED ^ 9)
+    d = DeviceCase(c)
+    first = raw_bits(_run_suffix(d)).copy()
+    assert maxnorm_rel(to_f64(d.out), d.oracle()) <= TOL["bf16"]
+    for it in range(200):
+        assert np.array_equal(raw_bits(_run_suffix(d)), first), it
+
+
 def test_suffix_call_causal_boundaries_bad_indices_and_shapes():
     c = wl.attention_case("suffix-causal", "bf16", [200, 90], [40, 1], 8, 2, 128, 16, seed=wl.SEED ^ 9)
     d = DeviceCase(c)
