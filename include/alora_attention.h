@@ -89,11 +89,13 @@ int alora_paged_attention_split(const void *q, const void *k_cache, const void *
  * The same computation for the rows of a projected suffix (Sec. 2.3 / 4.2: the tokens of an aLoRA
  * request that are not served from the cache, attending over the cached prefix and over each other):
  * batch rows that follow each other with the same sequence id and consecutive positions are handled
- * in blocks of 32 / (n_q_heads / n_kv_heads) rows that load every cached row once, on bf16 matrix
+ * in blocks of 128 / (n_q_heads / n_kv_heads) rows that load every cached row once, on bf16 matrix
  * instructions (the softmax weights are rounded to bf16 for the weighted sum of V; scores, maxima
  * and sums stay fp32).  Any batch is accepted -- rows that do not continue a run form blocks of
- * their own -- and results equal those of alora_paged_attention within the bf16 tolerance.
- * bf16 and head_dim 128 only (ALORA_ESHAPE otherwise); no workspace.
+ * their own -- and results equal those of alora_paged_attention within the bf16 tolerance; they do
+ * not depend on timing (repeated calls give the same bits).
+ * bf16 and head_dim 128 only (ALORA_ESHAPE otherwise); no workspace.  Block sizes that are not a
+ * multiple of 4 are served by the kernel of alora_paged_attention.
  */
 int alora_paged_attention_suffix(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                                  const int32_t *token_seq_ids, const int32_t *token_positions, void *out,

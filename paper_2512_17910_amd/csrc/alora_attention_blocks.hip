@@ -2,23 +2,29 @@
 // (a projected suffix attending over a cached prefix, Sec. 2.3 / 4.2) are handled by ONE workgroup per
 // K/V head, which loads every cached row once for all of them.  bf16, head_dim 128, on bf16 MFMA.
 //
-// A wavefront owns 32 columns (query row, query head of the K/V head's group): 32 / G rows; a workgroup
-// four times that.  Row blocks are cut at multiples of 128 / G of the POSITION, so whether a batch row leads a block is decided
-// from the row before it alone; the workgroups of the other rows exit at once.  A decode batch (every
-// row its own sequence) degenerates to one row per workgroup.
+// A wavefront owns 32 columns (query row, query head of the K/V head's group): 32 / G rows; the four
+// wavefronts of a workgroup 128 / G consecutive rows, which share the K and V tiles of 32 context positions
+// through LDS: every cached row is loaded once per 128 / G query rows.  Row blocks are cut at multiples of
+// 128 / G of the POSITION, so whether a batch row leads a block is decided from the row before it alone.
+// A workgroup owns a range of batch rows (chosen on the host: a whole row block for large batches, down to
+// one row for a decode batch, where every row leads a block of its own) and works through the blocks that
+// start in it; the range index is permuted so that the leading rows of a long run do not all fall to the
+// same shader engine.
 //
 // Per 32 context positions a wavefront runs two sets of 32x32x16 MFMAs that keep every column in one
 // lane pair from the scores to the output:
 //   scores^T [position x column] = K [position x d] . Q^T [d x column]   K rows from the LDS tile into the
 //       A operand (a lane holds 8 consecutive d of one position), Q held in registers;
 //   online softmax down each column: 16 accumulator registers per lane, one exchange between the two
-//       lanes of a column;
-//   out^T [d x column] += V^T [d x position] . P [position x column]   V goes through LDS and comes back
-//       with the transposing LDS load; P is the score accumulator itself, rounded to bf16 -- the B operand
-//       wants, per lane, the positions the accumulator registers of that lane already hold, up to an
-//       exchange of two position bits that is applied to the V rows when they are written to LDS.
-// The four wavefronts of a workgroup own 32 columns each (4 x 32 / G consecutive rows) and share the K and
-// V tiles of a block of 32 positions through LDS: every cached row is loaded once per 128 / G query rows.
+//       lanes of a column; no masking arithmetic on blocks that every column of the wavefront sees whole;
+//   out^T [d x column] += V^T [d x position] . P [position x column]   V comes back from LDS with the
+//       transposing load, whose two halves are taken eight rows apart: that hands a lane exactly the
+//       positions its score registers hold, so P is the score accumulator itself, rounded to bf16.
+// K and V rows go from global memory straight into LDS (no registers in between): four tile pairs, one being
+// multiplied while three are on their way, one barrier per 32 positions; the block-table entries of 64 such
+// steps sit in an LDS window.  An assembly statement never reads a register an MFMA writes (the compiler
+// cannot place the wait states for it); the copies and their wait counts are assembly because the compiler's
+// own bookkeeping would wait for all of them.
 #include "alora_attention_internal.h"
 
 namespace alora {

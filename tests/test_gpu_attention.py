@@ -270,6 +270,35 @@ def test_suffix_call_on_a_decode_batch_and_on_interleaved_rows():
     assert maxnorm_rel(out2, d2.oracle()) <= TOL["bf16"]
 
 
+def _mixed_batch(seed, n_q, n_kv, min_rows):
+    """Decode rows and projected suffixes of 2..70 rows side by side, short contexts: at least min_rows rows."""
+    rng = np.random.default_rng(seed)
+    rows, lens = [], []
+    while sum(rows) < min_rows:
+        r = 1 if rng.random() < 0.6 else int(rng.integers(2, 71))
+        rows.append(r)
+        lens.append(r + int(rng.integers(0, 150)))
+    return wl.attention_case(f"suffix-mixed-{n_q}-{n_kv}", "bf16", lens, rows, n_q, n_kv, 128, 16, seed=wl.SEED ^ seed)
+
+
+@pytest.mark.parametrize("heads", [(8, 8), (32, 8)])
+def test_suffix_call_on_a_batch_large_enough_for_whole_row_blocks_per_workgroup(heads):
+    """More than 8192 rows x 8 K/V heads: a workgroup then owns 32 batch rows and works through every block
+    that starts among them (decode rows: up to 32 blocks, runs: one or two), with the permuted range index
+    where a block spans several ranges (group size 1: 128 rows).  Sampled rows against the oracle, all rows
+    finite, and all rows equal to the per-row kernel's within the tolerance."""
+    c = _mixed_batch(77 + heads[0], heads[0], heads[1], 8300)
+    print(f"[case] {c.name} T={c.T}", flush=True)
+    d = DeviceCase(c)
+    out = to_f64(_run_suffix(d)).copy()
+    assert np.isfinite(out).all()
+    per_row = to_f64(d.run())
+    assert maxnorm_rel(out, per_row) <= TOL["bf16"]
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([rng.integers(0, c.T, 400), np.arange(64), np.arange(c.T - 64, c.T)]))
+    assert maxnorm_rel(out[rows], d.oracle(rows=rows)) <= TOL["bf16"]
+
+
 def test_suffix_call_gives_the_same_bits_on_every_call():
     """The row-block kernel takes no timing-dependent decision: 200 calls on one batch (blocks that need no
     mask, diagonal blocks, single rows), every one bit-identical to the first."""
