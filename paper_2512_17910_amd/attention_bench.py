@@ -5,9 +5,10 @@ positions (the positions of that configuration), bf16.  K/V caches of 2 x 1.07 G
 rows' contexts cover about half of them, far more than the on-package caches hold.
 
 Prints one JSON line with the roofline of the kernel (bound: HBM; algorithmic bytes = K and V rows
-of every row's context).  Parity at this size is checked by tests/test_gpu_attention.py.
+of every row's context; for the row-block kernel of --suffix the bf16 matrix unit, algorithmic flops =
+4 x head_dim per (query head, context position)).  Parity is checked by tests/test_gpu_attention.py.
 
-    python -m paper_2512_17910_amd.attention_bench [--steps K] [--warmup W] [--long]
+    python -m paper_2512_17910_amd.attention_bench [--steps K] [--warmup W] [--long | --few | --suffix ROWS]
 """
 from __future__ import annotations
 
@@ -118,6 +119,11 @@ def main() -> None:
                         "frac": io_bytes / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None, "kernel": "paged_attention_kernel<128, 4, true, true>",
                         "kernel_ms": ms, "algorithmic_bytes_per_launch": io_bytes}}
 
+    if "rowblocks" in name:
+        # the row-block kernel loads every cached row once per 128 / G query rows: its bound is the bf16 matrix unit
+        res["roofline"] = {"bound": "mfma", "achieved": res["tflops"], "peak": 2500.0, "unit": "TFLOP/s",
+                           "frac": res["tflops"] / 2500.0, "traffic": None, "kernel": "paged_attention_blocks_kernel<4>",
+                           "kernel_ms": ms, "algorithmic_flops_per_launch": flops}
     print(json.dumps(res))
 
 
