@@ -299,6 +299,20 @@ def test_suffix_call_on_a_batch_large_enough_for_whole_row_blocks_per_workgroup(
     assert maxnorm_rel(out[rows], d.oracle(rows=rows)) <= TOL["bf16"]
 
 
+def test_suffix_call_at_benchmark_size_on_sampled_rows():
+    """The row-block reader's benchmark shape (4 sequences of 16384 positions, the last 2048 of each are query
+    rows, 32 query / 8 K/V heads of 128, block size 16): every row finite, 40 sampled rows (first and last
+    rows of runs and of row blocks among them) against the oracle; the window of table entries is refilled
+    seven times per row block at this length."""
+    c = wl.attention_case("suffix-4x16384", "bf16", [16384] * 4, [2048] * 4, 32, 8, 128, 16, seed=wl.SEED ^ 91)
+    d = DeviceCase(c)
+    out = to_f64(_run_suffix(d))
+    assert np.isfinite(out).all()
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.r_[0, 31, 32, 2047, 2048, 4095 + 33, c.T - 1, rng.choice(c.T, 33, replace=False)])
+    assert maxnorm_rel(out[rows], d.oracle(rows=rows)) <= TOL["bf16"]
+
+
 def test_suffix_call_gives_the_same_bits_on_every_call():
     """The row-block kernel takes no timing-dependent decision: 200 calls on one batch (blocks that need no
     mask, diagonal blocks, single rows), every one bit-identical to the first."""
