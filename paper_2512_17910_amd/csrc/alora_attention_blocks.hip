@@ -38,11 +38,11 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 constexpr float AB_NEG_INF = -__builtin_inff();
 constexpr float AB_M_FLOOR = -1.0e30f;   // finite floor of the running maximum (scores below it weigh nothing)
 
-// four k of this lane's column, then the four that lie eight rows further on
+// four k of this lane's column, then the four that lie sixteen rows further on
 __device__ __forceinline__ bf16x8 read_tr_frag(const lds_byte *p, int pitch)
 {
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 8 * pitch));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 16 * pitch));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
@@ -67,47 +67,56 @@ __device__ __forceinline__ void load_lds16(uint32_t lds_addr, const void *base, 
 // (plain fmaxf, which the compiler fuses into v_max3_f32: an assembly statement that reads the registers
 // an MFMA has just written would miss the wait states the compiler places for instructions it knows)
 __device__ __forceinline__ float max3(float x, float y, float z) { return fmaxf(fmaxf(x, y), z); }
-// lo <- the value the lower 32 lanes hold in x, hi <- the upper 32 lanes' (each in all 64 lanes): one
-// v_permlane32_swap on two copies of x.  Assembly: the builtin of this name returned the first result twice.
+// Exchanges between the four lanes of a column (lanes c, c+16, c+32, c+48), as assembly statements (the
+// builtin of the 32-lane swap returned its first result twice) with wait states on both sides, which the
+// compiler cannot place for an instruction it does not see.  Checked with in-bounds probes:
+//   v_permlane16_swap on two copies of x: ev <- x of the even 16-lane row of this lane's row pair, od <- the odd row's
+//   v_permlane32_swap on two copies of x: lo <- x of the lower 32 lanes, hi <- the upper 32 lanes'
+__device__ __forceinline__ void row_pair(float x, float &ev, float &od)
+{
+    ev = x, od = x;
+    asm("s_nop 3\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 3" : "+v"(ev), "+v"(od));
+}
 __device__ __forceinline__ void both_halves(float x, float &lo, float &hi)
 {
     lo = x, hi = x;
-    // (wait states on both sides: the compiler does not see the instruction, so it cannot place the ones
-    // that a VALU write before it and a VALU read after it need)
     asm("s_nop 3\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 3" : "+v"(lo), "+v"(hi));
 }
-__device__ __forceinline__ float max_with_other_half(float x)
+__device__ __forceinline__ float max_over_column(float x)
 {
-    float lo, hi;
-    both_halves(x, lo, hi);
-    return max3(x, lo, hi);
+    float a, b, c, d;
+    row_pair(x, a, b);
+    both_halves(fmaxf(a, b), c, d);
+    return fmaxf(c, d);
 }
-__device__ __forceinline__ float sum_with_other_half(float x)
+__device__ __forceinline__ float sum_over_column(float x)
 {
-    float lo, hi;
-    both_halves(x, lo, hi);
-    return lo + hi;
+    float a, b, c, d;
+    row_pair(x, a, b);
+    both_halves(a + b, c, d);
+    return c + d;
 }
 
 // what a lane loads for a position that is not part of the context (the weighted sum multiplies it by 0)
 __device__ const uint32_t ab_zero_chunk[4] = {0u, 0u, 0u, 0u};
 
-template <int G>
-__global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs a, int R)
+template <int G, bool POW2>   // POW2: the block size is a power of two (shifts instead of divisions)
+__global__ __launch_bounds__(512, 4) void paged_attention_blocks_kernel(AttnArgs a, int R)
 {
     constexpr int D = 128;
-    constexpr int RBW = 32 / G;       // query rows per wavefront (32 columns = rows x heads of the group)
-    constexpr int RBG = 4 * RBW;      // query rows per workgroup
+    constexpr int NW = 8;             // wavefronts per workgroup
+    constexpr int RBW = 16 / G;       // query rows per wavefront (16 columns = rows x heads of the group)
+    constexpr int RBG = NW * RBW;     // query rows per workgroup
     constexpr int PITCH = 256;        // bytes per position row of the K and V tiles in LDS
     constexpr int TILE = 32 * PITCH;  // one tile: 32 positions
     constexpr int NB = 4;             // (K, V) tile pairs: one is multiplied while three are on their way
     __shared__ __attribute__((aligned(1024))) unsigned char tiles[NB * 2 * TILE];
-    __shared__ __attribute__((aligned(16))) unsigned char ok_bytes[NB][4];      // validity of the 32 positions of a pair: bit idx % 8 of byte idx / 8
-    __shared__ unsigned long long run_mask[4];
+    __shared__ __attribute__((aligned(16))) unsigned char ok_bytes[NB][NW];     // byte w: validity of positions 4w .. 4w+3 of a pair
+    __shared__ unsigned long long run_mask[2];
     constexpr int WIN = 64;            // blocks of 32 positions whose table entries the window below holds
     __shared__ int32_t window[WIN * 32 / 4 + 2];   // block sizes are multiples of 4
 
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const int hk = (int)blockIdx.x % a.Hkv;
     // ---- this workgroup's R batch rows (R a power of two <= 32, <= RBG) ------------------------------------
@@ -136,26 +145,28 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     const int Nkv = a.Hkv * D;
     const long long n_blocks = a.n_slots / a.bs;
     const long long cap = (long long)a.max_blocks * a.bs;
-    const int lr = lane >> 4, lq = lane & 15;
     const uint32_t tiles_at = (uint32_t)(uintptr_t)(lds_byte *)tiles;
-    // byte offsets of a lane's 16 bytes from the first of its instruction's four cache rows (ii = 0, 1; V: both)
-    const uint32_t row_off = (uint32_t)lr * (uint32_t)Nkv * 2u;
-    const uint32_t k_off0 = row_off + (uint32_t)((lq ^ ((8 * wu + lr) & 15)) << 4), k_off1 = row_off + (uint32_t)((lq ^ ((8 * wu + 4 + lr) & 15)) << 4);
-    const uint32_t v_off = row_off + (uint32_t)((lq ^ (lr << 2)) << 4);
-    // K fragment of k step s: row li, chunk 2s + lh
-    uint32_t k_r[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) k_r[s] = li * PITCH + (((2 * s + lh) ^ (li & 15)) << 4);
-    // V fragment of d tile t: the transposing read hands a lane k = 4lh .. 4lh+3 of its 16 (first read) and
-    // 8 + 4lh .. (second read, eight rows further on): the positions its score registers hold
-    uint32_t vaddr[4];
+    const uint32_t row_bytes = (uint32_t)Nkv * 2u, head_bytes = (uint32_t)hk * D * 2u;
+    const unsigned n_blocks_u = (unsigned)(n_blocks < 0x7fffffffll ? n_blocks : 0x7fffffffll);
+    // ---- copies global -> LDS: wavefront w fills positions 4w .. 4w+3 of a block of 32 with one K and one V
+    // instruction (one cache block: block sizes are multiples of 4, so its table entry is a scalar); lane ->
+    // position + lane / 16, physical 16-byte chunk lane % 16.
+    // K tile: row = position, the physical chunk holds logical chunk XOR (row % 16) (the score product reads
+    // one logical chunk of 16 rows).  V tile: row = position, XOR 4 * (row % 4) + 2 * (row / 4 % 2) (the
+    // transposing read takes two chunks of four rows per 16 lanes, rows 4 apart in the next 16 lanes).
+    const int row_c = 4 * wu + g4;                                   // this lane's position within a block of 32
+    const uint32_t row_off = (uint32_t)g4 * (uint32_t)Nkv * 2u;
+    const uint32_t k_off = row_off + (uint32_t)((c16 ^ (row_c & 15)) << 4);
+    const uint32_t v_off = row_off + (uint32_t)((c16 ^ (((row_c & 3) << 2) | (((row_c >> 2) & 1) << 1))) << 4);
+    // K fragment of position tile pt, k step ks: row 16pt + c16, chunk 4ks + g4 -> pt * 4096 + (k_base ^ (ks << 6))
+    const uint32_t k_base = (uint32_t)c16 * PITCH + (uint32_t)((g4 ^ c16) << 4);
+    // V fragment of d tile dt: rows 4g4 + j (then 16 further on), j = c16 / 4; the 8 bytes of d = 16dt + 4(c16 % 4) ..
+    // -> v_base ^ (dt << 5)
+    uint32_t v_base;
     {
-        const int s16 = lane & 15, j = s16 >> 2, blk = (lane >> 4) & 1;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int chunk = 4 * t + 2 * blk + ((s16 & 3) >> 1);
-            vaddr[t] = (uint32_t)(4 * lh + j) * PITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s16 & 1) << 3);
-        }
+        const int j = c16 >> 2, vrow = 4 * g4 + j;
+        const int swz = (j << 2) | ((g4 & 1) << 1);
+        v_base = (uint32_t)vrow * PITCH + (uint32_t)((swz ^ ((c16 & 3) >> 1)) << 4) + (uint32_t)((c16 & 1) << 3);
     }
 
   for (bool first = true; leaders; leaders &= leaders - 1, first = false) {
@@ -170,11 +181,11 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
         bool cont = tid == 0;
         if (tid > 0 && tid < limit && t0 + tid < a.T) cont = a.seq[t0 + tid] == sq && a.pos[t0 + tid] == p0 + tid;
         const unsigned long long mk = __builtin_amdgcn_ballot_w64(cont);
-        if (lane == 0) run_mask[w] = mk;
+        if (lane == 0 && w < 2) run_mask[w] = mk;
         __syncthreads();
         nrows = 0;
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) {
+        for (int ww = 0; ww < 2; ++ww) {
             const unsigned long long mw = run_mask[ww];
             if (nrows == 64 * ww) nrows += mw == ~0ull ? 64 : __builtin_ctzll(~mw);
         }
@@ -186,157 +197,145 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
     const int32_t *bt = a.bt + (size_t)(row_ok ? sq : 0) * a.max_blocks;
 
     // this lane's column: query row r_j of the block (rows w*RBW .. of this wavefront), query head g_j
-    const int r_j = w * RBW + li / G, g_j = li % G;
+    const int r_j = w * RBW + c16 / G, g_j = c16 % G;
     const bool col_ok = row_ok && r_j < nrows;
     const int lim_j = col_ok ? p0 + r_j : -1;                        // last position the column attends to
     const int lim_w = (row_ok && wu * RBW < nrows) ? p0 + min((wu + 1) * RBW, nrows) - 1 : -1;   // ... and any column of this wavefront
     const int lim_first = p0 + wu * RBW;                             // ... and the wavefront's first column
     const size_t q_at = ((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * D;
-    bf16x8 qf[8];
+    bf16x8 qf[4];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < 4; ++s) {
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (col_ok) v = *(const u32x4 *)((const bf16_t *)a.q + q_at + 16 * s + 8 * lh);
+        if (col_ok) v = *(const u32x4 *)((const bf16_t *)a.q + q_at + 32 * s + 8 * g4);
         qf[s] = __builtin_bit_cast(bf16x8, v);
     }
     // (a use of the query registers ahead of the loop: the compiler places its wait for these loads here and
     // not in front of the first MFMA of every step, where it would also wait for the copies in flight)
 #pragma unroll
-    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
+    for (int s = 0; s < 4; ++s) asm volatile("" : "+v"(qf[s]));
 
-    f32x16 acc[4];
+    f32x4 acc[8];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 8; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+        for (int e = 0; e < 4; ++e) acc[t][e] = 0.f;
     float m = AB_M_FLOOR, l = 0.f;
 
-    // ---- copies global -> LDS: wavefront w fills positions 8w .. 8w+7 of a block of 32 with two K and two V
-    // instructions; instruction ii covers positions 8w + 4ii .. +3 (one cache block: block sizes are multiples
-    // of 4, so its table entry is a scalar), lane -> position + lane / 16, physical 16-byte chunk lane % 16.
-    // K tile: row = position, the physical chunk holds logical chunk XOR (row % 16) (the score product reads
-    // one logical chunk of 32 rows).  V tile: row = position, XOR 4 * (row % 4) (transposing read).
     // Table entries come from a window in LDS that holds those of WIN blocks of 32 positions and is refilled
     // by the whole workgroup when the lookups reach its end (the index of four aligned positions is the same
     // in every lane); an entry past the context reads as -1.
-    auto entry_of = [&](int pu) { return a.bs_shift >= 0 ? (pu >> a.bs_shift) : (pu / a.bs); };
+    auto entry_of = [&](int pu) { return POW2 ? (pu >> a.bs_shift) : (pu / a.bs); };
     int win_first = 0;                       // table index of window[0]
     auto refill = [&](int cw) {              // entries of blocks cw .. cw + WIN - 1; all wavefronts call it together
         win_first = entry_of(32 * cw);
         const int last = entry_of(min(32 * (cw + WIN), n_ctx) - 1);      // n_ctx > 32 * cw whenever this is called
         __syncthreads();
-        for (int i = tid; win_first + i <= last; i += 256) window[i] = bt[win_first + i];
+        for (int i = tid; win_first + i <= last; i += 64 * NW) window[i] = bt[win_first + i];
         __syncthreads();
     };
-    auto lookup = [&](int cb, int ii) {
-        const int pu = cb + 8 * wu + 4 * ii;
+    auto lookup = [&](int cb) {
+        const int pu = cb + 4 * wu;
         return pu < n_ctx ? __builtin_amdgcn_readfirstlane(window[entry_of(pu) - win_first]) : -1;
     };
-    auto issue = [&](int c, int blk0, int blk1) {
-        const int cb = 32 * c;
-        const uint32_t pair_at = tiles_at + (uint32_t)(c & (NB - 1)) * (2 * TILE);
-        unsigned okb = 0;
-#pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-            const int blk = ii ? blk1 : blk0;
-            const int pu = cb + 8 * wu + 4 * ii;                    // first of the four positions
-            const bool blk_ok = blk >= 0 && blk < n_blocks;
+    // (the scalar unit of a CU serves all its wavefronts: what a wavefront computes per step besides the
+    // matrix and vector work is kept to a few instructions)
+    auto issue = [&](int c, int blk) {
+        const int pu = 32 * c + 4 * wu;                          // first of the four positions
+        const uint32_t k_to = tiles_at + ((uint32_t)(c & (NB - 1)) << 14) + ((uint32_t)wu << 10), v_to = k_to + TILE;
+        static_assert(2 * TILE == 1 << 14 && 4 * PITCH == 1 << 10, "tile geometry");
+        unsigned okb = 0xfu;
+        if ((unsigned)blk < n_blocks_u && pu + 4 <= n_ctx) {   // the usual case: scalar base, the lane's constant offset
+            const unsigned slot = (POW2 ? ((unsigned)blk << a.bs_shift) : (unsigned)blk * (unsigned)a.bs) + (unsigned)(POW2 ? (pu & (a.bs - 1)) : (pu % a.bs));
+            const unsigned long long at = (unsigned long long)slot * row_bytes + head_bytes;   // first of the four cache rows
+            load_lds16(k_to, (const char *)a.kc + at, k_off);
+            load_lds16(v_to, (const char *)a.vc + at, v_off);
+        } else {           // rows that are not part of the context read 16 zero bytes
+            const bool blk_ok = (unsigned)blk < n_blocks_u;
             const int n_ok = blk_ok ? max(0, min(4, n_ctx - pu)) : 0;
-            okb |= ((1u << n_ok) - 1u) << (4 * ii);
-            const int off = a.bs_shift >= 0 ? (pu & (a.bs - 1)) : (pu % a.bs);
-            const size_t at = ((size_t)(blk_ok ? blk : 0) * a.bs + off) * Nkv + (size_t)hk * D;   // first of the four cache rows
-            const uint32_t k_to = pair_at + (uint32_t)(8 * wu + 4 * ii) * PITCH, v_to = k_to + TILE;
-            if (n_ok == 4) {   // the usual case: scalar base, the lane's constant offset
-                load_lds16(k_to, (const bf16_t *)a.kc + at, ii ? k_off1 : k_off0);
-                load_lds16(v_to, (const bf16_t *)a.vc + at, v_off);
-            } else {           // rows that are not part of the context read 16 zero bytes
-                const bool have = lr < n_ok;
-                const void *kp = have ? (const void *)((const char *)((const bf16_t *)a.kc + at) + (ii ? k_off1 : k_off0)) : (const void *)ab_zero_chunk;
-                const void *vp = have ? (const void *)((const char *)((const bf16_t *)a.vc + at) + v_off) : (const void *)ab_zero_chunk;
-                load_lds16(k_to, kp);
-                load_lds16(v_to, vp);
-            }
+            okb = (1u << n_ok) - 1u;
+            const unsigned slot = (blk_ok ? (unsigned)blk * (unsigned)a.bs : 0u) + (unsigned)(pu % a.bs);
+            const unsigned long long at = (unsigned long long)slot * row_bytes + head_bytes;
+            const bool have = g4 < n_ok;
+            const void *kp = have ? (const void *)((const char *)a.kc + at + k_off) : (const void *)ab_zero_chunk;
+            const void *vp = have ? (const void *)((const char *)a.vc + at + v_off) : (const void *)ab_zero_chunk;
+            load_lds16(k_to, kp);
+            load_lds16(v_to, vp);
         }
-        if (lane == 0) ok_bytes[c & (NB - 1)][wu] = (unsigned char)okb;
+        ok_bytes[c & (NB - 1)][wu] = (unsigned char)okb;      // (every lane writes the same byte)
     };
 
     auto consume = [&](int c) {
         const int cb = 32 * c;
         const lds_byte *kb = (const lds_byte *)tiles + (c & (NB - 1)) * (2 * TILE), *vb = kb + TILE;
-        // ---- scores^T = K . Q^T ------------------------------------------------------------------
-        f32x16 sc;
+        // ---- scores^T = K . Q^T : two tiles of 16 positions ------------------------------------------
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sc[e] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8 *)(kb + k_r[s]);
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sc, 0, 0, 0);
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 k0 = *(const __attribute__((address_space(3))) bf16x8 *)(kb + (k_base ^ (uint32_t)(ks << 6)));
+            const bf16x8 k1 = *(const __attribute__((address_space(3))) bf16x8 *)(kb + 16 * PITCH + (k_base ^ (uint32_t)(ks << 6)));
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[ks], s1, 0, 0, 0);
         }
-        bf16x8 vf[2][4];
+        // ---- softmax down this lane's column (its 32 positions sit in four lanes) --------------------
+        __builtin_amdgcn_s_setprio(2);   // the vector arithmetic of this wavefront goes ahead of wavefronts waiting for the matrix unit
+        const u32x2 ob = *(const u32x2 *)ok_bytes[c & (NB - 1)];
+        const unsigned ok_lo = __builtin_amdgcn_readfirstlane(ob.x), ok_hi = __builtin_amdgcn_readfirstlane(ob.y);
+        float sc[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        if (!((ok_lo & ok_hi) == 0x0f0f0f0fu && cb + 31 <= lim_first)) {   // a block that every column of the wavefront sees whole needs no mask
+            auto nibbles = [](unsigned x) { x |= x >> 4; return (x & 0xffu) | ((x >> 8) & 0xff00u); };
+            const unsigned okmask = nibbles(ok_lo) | (nibbles(ok_hi) << 16);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) vf[ks][t] = read_tr_frag(vb + vaddr[t] + ks * 16 * PITCH, PITCH);
-        // ---- softmax down this lane's column -----------------------------------------------------
-        const unsigned okmask = __builtin_amdgcn_readfirstlane(*(const unsigned *)ok_bytes[c & (NB - 1)]);
-        if (!(okmask == 0xffffffffu && cb + 31 <= lim_first)) {   // a block that every column of the wavefront sees whole needs no mask
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int idx = 8 * (v >> 2) + 4 * lh + (v & 3);
+            for (int v = 0; v < 8; ++v) {
+                const int idx = 16 * (v >> 2) + 4 * g4 + (v & 3);
                 const bool on = ((okmask >> idx) & 1u) && cb + idx <= lim_j;
                 sc[v] = on ? sc[v] : AB_NEG_INF;
             }
         }
-        float mx = max3(sc[0], sc[1], sc[2]);
-#pragma unroll
-        for (int v = 3; v < 15; v += 2) mx = max3(mx, sc[v], sc[v + 1]);
-        mx = max_with_other_half(fmaxf(mx, sc[15]));
+        float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        mx = max_over_column(mx);
         const float mn = fmaxf(m, mx * a.scale_log2e);
         const float corr = __builtin_amdgcn_exp2f(m - mn);
         m = mn;
         float ps = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+        for (int v = 0; v < 8; ++v) {
             sc[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[v], a.scale_log2e, -mn));
             ps += sc[v];
         }
         l = l * corr + ps;
         if (__builtin_amdgcn_ballot_w64(corr != 1.f)) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < 8; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[t][e] *= corr;
+                for (int e = 0; e < 4; ++e) acc[t][e] *= corr;
         }
-        // ---- out^T += V^T . P : P straight from the score registers --------------------------------
+        // ---- out^T += V^T . P : P straight from the score registers (positions 4g4 .. +3 and 16 + 4g4 .. +3) --
+        const u32x4 pv = {pack_bf16(sc[0], sc[1]), pack_bf16(sc[2], sc[3]), pack_bf16(sc[4], sc[5]), pack_bf16(sc[6], sc[7])};
+        __builtin_amdgcn_s_setprio(0);
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const u32x4 pv = {pack_bf16(sc[8 * ks + 0], sc[8 * ks + 1]), pack_bf16(sc[8 * ks + 2], sc[8 * ks + 3]),
-                              pack_bf16(sc[8 * ks + 4], sc[8 * ks + 5]), pack_bf16(sc[8 * ks + 6], sc[8 * ks + 7])};
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pv);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks][t], pf, acc[t], 0, 0, 0);
-        }
+        for (int t = 0; t < 8; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(read_tr_frag(vb + (v_base ^ (uint32_t)(t << 5)), PITCH), pf, acc[t], 0, 0, 0);
     };
 
-    // ---- the context, 32 positions at a time: all four wavefronts share the tiles -------------------
+    // ---- the context, 32 positions at a time: all eight wavefronts share the tiles ------------------
     // Block c lives in tile pair c % 4.  In the step of block c every wavefront waits for its own copies of
-    // block c (those of c+1 and c+2, four instructions each, stay in flight), the barrier makes that hold for
+    // block c (those of c+1 and c+2, two instructions each, stay in flight), the barrier makes that hold for
     // all of them and tells that block c-1 has been multiplied by everyone; its pair then takes the copies of
-    // block c+3, whose table entries were looked up a step earlier.  Blocks past the context are copied too (all
+    // block c+3, whose table entry was looked up a step earlier.  Blocks past the context are copied too (all
     // zeros, from one 16-byte constant), which keeps the count of copies in flight the same in every step.
     {
         if (n_chunks > 0) refill(0);
 #pragma unroll
-        for (int k = 0; k < NB - 1; ++k) issue(k, lookup(32 * k, 0), lookup(32 * k, 1));
-        int b0 = lookup(32 * (NB - 1), 0), b1 = lookup(32 * (NB - 1), 1);
+        for (int kk = 0; kk < NB - 1; ++kk) issue(kk, lookup(32 * kk));
+        int b0 = lookup(32 * (NB - 1));
         auto step = [&](int c) {
-            // this wavefront's copies of block c have landed (eight newer ones may be in flight); behind the
-            // barrier that holds for every wavefront, and all of them are done with block c-1
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            issue(c + NB - 1, b0, b1);
+            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            issue(c + NB - 1, b0);
             const int cn = c + NB;
             if ((cn & (WIN - 1)) == 0 && 32 * cn < n_ctx) refill(cn);
-            b0 = lookup(32 * cn, 0), b1 = lookup(32 * cn, 1);
+            b0 = lookup(32 * cn);
         };
         // (two loops: the accumulators live in the first only)
         const int n_chunks_w = lim_w >= 0 ? (lim_w >> 5) + 1 : 0;
@@ -350,20 +349,17 @@ __global__ __launch_bounds__(256, 2) void paged_attention_blocks_kernel(AttnArgs
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
-    // ---- the two lanes of a column add their weight sums; normalise and store ----------------------
-    l = sum_with_other_half(l);
+    // ---- the four lanes of a column add their weight sums; normalise and store ---------------------
+    l = sum_over_column(l);
     // a row that is not valid leads a block of its own and gets zeros
-    if (col_ok || (!row_ok && w == 0 && li < G)) {
+    if (col_ok || (!row_ok && w == 0 && c16 < G)) {
         const float inv = l > 0.f ? 1.f / l : 0.f;
         bf16_t *orow = (bf16_t *)a.out + ((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * D;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const u32x2 o = {pack_bf16(acc[t][4 * b + 0] * inv, acc[t][4 * b + 1] * inv),
-                                 pack_bf16(acc[t][4 * b + 2] * inv, acc[t][4 * b + 3] * inv)};
-                *(u32x2 *)(orow + 32 * t + 8 * b + 4 * lh) = o;
-            }
+        for (int t = 0; t < 8; ++t) {
+            const u32x2 o = {pack_bf16(acc[t][0] * inv, acc[t][1] * inv), pack_bf16(acc[t][2] * inv, acc[t][3] * inv)};
+            *(u32x2 *)(orow + 16 * t + 4 * g4) = o;
+        }
     }
   }
 }
@@ -374,14 +370,19 @@ int launch_attention_blocks(const AttnArgs &a, int G, hipStream_t stream)
     // small batches (a decode batch: every row leads a block of its own)
     int R = 32 / G * 4 < 32 ? 32 / G * 4 : 32;
     while (R > 1 && (long long)((a.T + R - 1) / R) * a.Hkv < 2048) R /= 2;
-    const dim3 grid((unsigned)((a.T + R - 1) / R) * (unsigned)a.Hkv), block(256);
+    const dim3 grid((unsigned)((a.T + R - 1) / R) * (unsigned)a.Hkv), block(512);
+    const bool pow2 = a.bs_shift >= 0;
+#define AB_LAUNCH(GG) \
+    if (pow2) hipLaunchKernelGGL((paged_attention_blocks_kernel<GG, true>), grid, block, 0, stream, a, R); \
+    else hipLaunchKernelGGL((paged_attention_blocks_kernel<GG, false>), grid, block, 0, stream, a, R)
     switch (G) {
-    case 1: hipLaunchKernelGGL(paged_attention_blocks_kernel<1>, grid, block, 0, stream, a, R); break;
-    case 2: hipLaunchKernelGGL(paged_attention_blocks_kernel<2>, grid, block, 0, stream, a, R); break;
-    case 4: hipLaunchKernelGGL(paged_attention_blocks_kernel<4>, grid, block, 0, stream, a, R); break;
-    case 8: hipLaunchKernelGGL(paged_attention_blocks_kernel<8>, grid, block, 0, stream, a, R); break;
+    case 1: AB_LAUNCH(1); break;
+    case 2: AB_LAUNCH(2); break;
+    case 4: AB_LAUNCH(4); break;
+    case 8: AB_LAUNCH(8); break;
     default: return (int)hipErrorInvalidValue;
     }
+#undef AB_LAUNCH
     return (int)hipGetLastError();
 }
 
