@@ -122,7 +122,7 @@ def main() -> None:
     if "rowblocks" in name:
         # the row-block kernel loads every cached row once per 128 / G query rows: its bound is the bf16 matrix unit
         res["roofline"] = {"bound": "mfma", "achieved": res["tflops"], "peak": 2500.0, "unit": "TFLOP/s",
-                           "frac": res["tflops"] / 2500.0, "traffic": None, "kernel": "paged_attention_blocks_kernel<4>",
+                           "frac": res["tflops"] / 2500.0, "traffic": None, "kernel": "paged_attention_blocks_kernel<4, true>",
                            "kernel_ms": ms, "algorithmic_flops_per_launch": flops}
     print(json.dumps(res))
 

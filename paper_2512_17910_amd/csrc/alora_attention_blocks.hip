@@ -2,7 +2,7 @@
 // (a projected suffix attending over a cached prefix, Sec. 2.3 / 4.2) are handled by ONE workgroup per
 // K/V head, which loads every cached row once for all of them.  bf16, head_dim 128, on bf16 MFMA.
 //
-// A wavefront owns 32 columns (query row, query head of the K/V head's group): 32 / G rows; the four
+// A wavefront owns 16 columns (query row, query head of the K/V head's group): 16 / G rows; the eight
 // wavefronts of a workgroup 128 / G consecutive rows, which share the K and V tiles of 32 context positions
 // through LDS: every cached row is loaded once per 128 / G query rows.  Row blocks are cut at multiples of
 // 128 / G of the POSITION, so whether a batch row leads a block is decided from the row before it alone.
@@ -11,15 +11,16 @@
 // start in it; the range index is permuted so that the leading rows of a long run do not all fall to the
 // same shader engine.
 //
-// Per 32 context positions a wavefront runs two sets of 32x32x16 MFMAs that keep every column in one
-// lane pair from the scores to the output:
-//   scores^T [position x column] = K [position x d] . Q^T [d x column]   K rows from the LDS tile into the
-//       A operand (a lane holds 8 consecutive d of one position), Q held in registers;
-//   online softmax down each column: 16 accumulator registers per lane, one exchange between the two
+// Per 32 context positions a wavefront runs two sets of 16x16x32 MFMAs that keep every column in the same
+// four lanes (c, c+16, c+32, c+48) from the scores to the output:
+//   scores^T [position x column] = K [position x d] . Q^T [d x column]   two tiles of 16 positions; K rows
+//       from the LDS tile into the A operand (a lane holds 8 consecutive d of one position), Q in registers;
+//   online softmax down each column: 8 accumulator registers per lane, two exchanges between the four
 //       lanes of a column; no masking arithmetic on blocks that every column of the wavefront sees whole;
-//   out^T [d x column] += V^T [d x position] . P [position x column]   V comes back from LDS with the
-//       transposing load, whose two halves are taken eight rows apart: that hands a lane exactly the
-//       positions its score registers hold, so P is the score accumulator itself, rounded to bf16.
+//   out^T [d x column] += V^T [d x position] . P [position x column]   eight tiles of 16 d; V comes back
+//       from LDS with the transposing load, whose two halves are taken sixteen rows apart: that hands a
+//       lane exactly the positions its score registers hold, so P is the score accumulator itself, rounded
+//       to bf16.
 // K and V rows go from global memory straight into LDS (no registers in between): four tile pairs, one being
 // multiplied while three are on their way, one barrier per 32 positions; the block-table entries of 64 such
 // steps sit in an LDS window.  An assembly statement never reads a register an MFMA writes (the compiler
@@ -64,9 +65,6 @@ __device__ __forceinline__ void load_lds16(uint32_t lds_addr, const void *base, 
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voffset), "s"(base) : "memory");
 }
-// (plain fmaxf, which the compiler fuses into v_max3_f32: an assembly statement that reads the registers
-// an MFMA has just written would miss the wait states the compiler places for instructions it knows)
-__device__ __forceinline__ float max3(float x, float y, float z) { return fmaxf(fmaxf(x, y), z); }
 // Exchanges between the four lanes of a column (lanes c, c+16, c+32, c+48), as assembly statements (the
 // builtin of the 32-lane swap returned its first result twice) with wait states on both sides, which the
 // compiler cannot place for an instruction it does not see.  Checked with in-bounds probes:
