@@ -15,7 +15,7 @@ from gpu_util import TOL, maxnorm_rel, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
-HIDDEN, NQH, NKVH, HD, L, RANK, BS, N_BLOCKS, VOCAB = 256, 4, 2, 64, 3, 16, 16, 40, 97
+HIDDEN, NQH, NKVH, HD, L, RANK, BS, N_BLOCKS, VOCAB = 256, 4, 2, 128, 3, 16, 16, 40, 97
 NQ, NKV = NQH * HD, NKVH * HD
 NEVER = 1 << 30
 
@@ -153,7 +153,14 @@ def _attend(m: TinyModel, planner, rid, q, positions):
     assert ab.alora_paged_attention_validate(bt, seq, pos, dims) == ab.ALORA_OK
     ab.alora_paged_attention(q, m.kc, m.vc, bt, seq, pos, out, dims)
     torch.cuda.synchronize()
-    return to_f64(out)
+    got = to_f64(out)
+    if m.dtype == "bf16":
+        # the same rows through the row-block reader of projected suffixes (consecutive positions of one sequence)
+        out2 = torch.full_like(q, float("nan"))
+        ab.alora_paged_attention_suffix(q, m.kc, m.vc, bt, seq, pos, out2, dims)
+        torch.cuda.synchronize()
+        assert maxnorm_rel(to_f64(out2), got) <= TOL["bf16"]
+    return got
 
 
 def _dense_attention(m: TinyModel, tokens, adapter, start, positions):
