@@ -425,3 +425,11 @@ def attention_case(name: str, dtype: str, seq_lens: Sequence[int], rows_per_seq:
         kc, vc = f32_to_bf16_bits(kc), f32_to_bf16_bits(vc)
     return AttentionCase(name, dtype, n_q_heads, n_kv_heads, head_dim, block_size, q, kc, vc, bt,
                          np.asarray(seq, np.int32), np.asarray(pos, np.int32), lens)
+
+
+def rope_table(max_pos: int, head_dim: int, base: float = 10000.0) -> Tuple[np.ndarray, np.ndarray]:
+    """(cos, sin) fp32 [max_pos, head_dim / 2] of the angles position * base ** (-2 i / head_dim): the table a
+    serving engine keeps as a constant buffer of the model and hands to the projection as an input."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    ang = np.arange(max_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / head_dim)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
