@@ -155,6 +155,17 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
  *                  that holds no such results gives wrong outputs (indices read from it are range-
  *                  checked, so nothing outside the buffers is touched).  Decode-sized bf16 batches
  *                  regroup inside the projection kernel anyway; the flag changes nothing there.
+ *   rope_cos/_sin  the step between the projection and the cache write in a served Llama-family layer, fused
+ *                  into the store (the paper is silent on positions; Sec. 2.1): within every q and k head,
+ *                  features i and i + head_dim/2 of row t are turned by the angle whose cosine and sine
+ *                  the tables hold at [token_positions[t], i]:
+ *                      out[i] = y[i] cos - y[i + head_dim/2] sin,  out[i + head_dim/2] = y[i + head_dim/2] cos + y[i] sin
+ *                  in fp32 on the unrounded projection output (adapter term and bias included), rounded
+ *                  once; v is not rotated.  Rows before the activation point stay bit-identical to those
+ *                  of a base-only call with the same tables.  token_positions must lie in
+ *                  [0, rope_positions) (a position outside reads the nearest table row; alora_qkv_validate
+ *                  does not know the tables).  bf16 path: head_dim 128 only (ALORA_ESHAPE otherwise);
+ *                  fp32 path: any even head_dim.
  * Per-module factors (separate A^Q, A^K, A^V with B^Q, B^K, B^V; Sec. 2.3) are the block-structured
  * special case: A = [A^Q | A^K | A^V] of rank 3r and B with B^Q, B^K, B^V on its block diagonal.
  */
@@ -162,6 +173,9 @@ typedef struct alora_extras {
     const void *bias;
     const int32_t *adapter_ranks;
     int32_t reuse_grouping;
+    const float *rope_cos;    /* DEVICE fp32 [rope_positions, head_dim / 2], 16-byte aligned, or NULL: no rotation */
+    const float *rope_sin;    /* the same shape; both or neither                                                  */
+    int32_t rope_positions;   /* rows of the two tables                                                           */
 } alora_extras;
 int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
                          const void *W_qkv, const void *const *A, const void *const *B,

@@ -33,7 +33,8 @@ class AloraWsLayout(ctypes.Structure):
 
 
 class AloraExtras(ctypes.Structure):
-    _fields_ = [("bias", ctypes.c_void_p), ("adapter_ranks", ctypes.c_void_p), ("reuse_grouping", ctypes.c_int32)]
+    _fields_ = [("bias", ctypes.c_void_p), ("adapter_ranks", ctypes.c_void_p), ("reuse_grouping", ctypes.c_int32),
+                ("rope_cos", ctypes.c_void_p), ("rope_sin", ctypes.c_void_p), ("rope_positions", ctypes.c_int32)]
 
 
 class AloraAttnDims(ctypes.Structure):
@@ -191,11 +192,15 @@ def alora_qkv_forward(x, token_adapter_ids, activation_start, W_qkv, A: Sequence
 
 def alora_qkv_forward_ex(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
                          q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims,
-                         workspace, bias=None, adapter_ranks=None, stream=None, reuse_grouping: bool = False) -> None:
+                         workspace, bias=None, adapter_ranks=None, stream=None, reuse_grouping: bool = False,
+                         rope=None) -> None:
     """alora_qkv_forward with a layer bias [N] (device tensor) and/or one rank per adapter (host ints);
     reuse_grouping: use the classification/grouping an earlier call left in this workspace for the same
-    token batch (the per-layer call of a model whose layers share one batch)."""
-    ex = AloraExtras(_ptr(bias), None, 1 if reuse_grouping else 0)
+    token batch (the per-layer call of a model whose layers share one batch); rope: (cos, sin) fp32 device
+    tensors [positions, head_dim / 2]: rotary embedding of q and k fused into the store."""
+    ex = AloraExtras(_ptr(bias), None, 1 if reuse_grouping else 0, None, None, 0)
+    if rope is not None:
+        ex.rope_cos, ex.rope_sin, ex.rope_positions = _ptr(rope[0]), _ptr(rope[1]), int(rope[0].shape[0])
     keep = None
     if adapter_ranks is not None:
         keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])
@@ -211,12 +216,14 @@ def alora_qkv_forward_ex(x, token_adapter_ids, activation_start, W_qkv, A: Seque
 
 def alora_qkv_graph_create(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
                            q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims, workspace,
-                           bias=None, adapter_ranks=None):
+                           bias=None, adapter_ranks=None, rope=None):
     """Record one forward call with these buffers into a HIP graph; returns an opaque handle for
     alora_qkv_graph_launch / alora_qkv_graph_destroy.  The caller keeps every tensor alive and rewrites
     their contents in place between launches."""
     h = ctypes.c_void_p(None)
-    ex = AloraExtras(_ptr(bias), None, 0)
+    ex = AloraExtras(_ptr(bias), None, 0, None, None, 0)
+    if rope is not None:
+        ex.rope_cos, ex.rope_sin, ex.rope_positions = _ptr(rope[0]), _ptr(rope[1]), int(rope[0].shape[0])
     keep = None
     if adapter_ranks is not None:
         keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])

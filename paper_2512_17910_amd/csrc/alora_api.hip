@@ -211,6 +211,11 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
     if (extras) {
         bias = extras->bias;
         if (bias && misaligned16(bias)) return ALORA_EINVAL;
+        if ((extras->rope_cos != nullptr) != (extras->rope_sin != nullptr)) return ALORA_EINVAL;
+        if (extras->rope_cos) {
+            if (misaligned16(extras->rope_cos) || misaligned16(extras->rope_sin) || extras->rope_positions < 1) return ALORA_EINVAL;
+            if (dims->head_dim % 2 || (dims->dtype == ALORA_BF16 && dims->head_dim != 128)) return ALORA_ESHAPE;
+        }
         if (extras->adapter_ranks) {
             for (int i = 0; i < dims->n_adapters; ++i) {
                 const int ri = extras->adapter_ranks[i];
@@ -229,6 +234,8 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
     fill_common(f, dims, l, workspace, hip_stream);
     f.bias = bias;
     f.ranks = ranks;
+    f.D = dims->head_dim;
+    if (extras && extras->rope_cos) { f.rope_cos = extras->rope_cos; f.rope_sin = extras->rope_sin; f.rope_positions = extras->rope_positions; }
     f.block_size = block_size;
     f.x = x; f.W = W_qkv; f.aid = token_adapter_ids; f.start = activation_start; f.slot = slot_mapping;
     f.q = q_out; f.kc = k_cache; f.vc = v_cache;
@@ -243,6 +250,7 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
             e = launch_shrink_f32(f, ta);
             if (!e && timed) e = (int)hipEventRecord(g_prof.ev0[g_prof.used], f.stream);
             if (!e) e = launch_gemm_f32(f, tb);
+            if (!e && f.rope_cos) e = launch_rope_f32(f);
             if (!e && timed) e = (int)hipEventRecord(g_prof.ev1[g_prof.used], f.stream);
         } else {
             if (!prep_inside) e = launch_shrink_bf16(f, ta);

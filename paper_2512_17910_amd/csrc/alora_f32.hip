@@ -111,6 +111,39 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     }
 }
 
+// Rotary embedding on the fp32 path: the q_out rows and the K slots this call wrote, turned in place.  The
+// stored values are the unrounded fp32 outputs, so this equals a rotation fused into the store.  One
+// workgroup per token row; a thread takes the pairs (i, i + D/2) of the q heads and then of the k heads.
+__global__ __launch_bounds__(256) void rope_f32_kernel(float *__restrict__ q, float *__restrict__ kc,
+                                                       const int64_t *__restrict__ slot, const int32_t *__restrict__ pos,
+                                                       const float *__restrict__ cs, const float *__restrict__ sn,
+                                                       int n_pos, int Nq, int Nkv, int D)
+{
+    const int t = blockIdx.x, half = D / 2;
+    const int p = min(max(pos[t], 0), n_pos - 1);
+    const int64_t sl = slot[t];
+    const int pairs = (Nq + Nkv) / 2;
+    for (int idx = threadIdx.x; idx < pairs; idx += 256) {
+        const int h = idx / half, i = idx % half;
+        float *row;
+        if (h * D < Nq) row = q + (size_t)t * Nq + h * D;
+        else if (sl >= 0) row = kc + (size_t)sl * Nkv + (h * D - Nq);
+        else continue;
+        const float c = cs[(size_t)p * half + i], s = sn[(size_t)p * half + i];
+        const float a = row[i], b = row[i + half];
+        row[i] = a * c - b * s;
+        row[i + half] = b * c + a * s;
+    }
+}
+
+int launch_rope_f32(const Fwd &f)
+{
+    if (f.T == 0) return 0;
+    hipLaunchKernelGGL(rope_f32_kernel, dim3(f.T), dim3(256), 0, f.stream, (float *)f.q, (float *)f.kc, f.slot, f.pos,
+                       f.rope_cos, f.rope_sin, f.rope_positions, f.Nq, f.Nkv, f.D);
+    return (int)hipGetLastError();
+}
+
 int launch_shrink_f32(const Fwd &f, const PtrTable &A)
 {
     if (f.T == 0 || f.L == 0) return 0;

@@ -32,7 +32,9 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
                                                            const int4 *__restrict__ blocktab,
                                                            const int64_t *__restrict__ slot, bf16_t *__restrict__ q,
                                                            bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int T, int Nq,
-                                                           int Nkv, int L, int r)
+                                                           int Nkv, int L, int r, const float *__restrict__ rope_cos,
+                                                           const float *__restrict__ rope_sin, const int32_t *__restrict__ pos,
+                                                           int rope_positions)
 {
     const float *S_part = (const float *)S_any;
     __shared__ float s_lds[32][ALORA_MAX_RANK + 1];
@@ -130,6 +132,25 @@ __global__ __launch_bounds__(1024) void finish_bf16_kernel(const float *__restri
 #pragma unroll
         for (int e = 0; e < 8; ++e) y[e] += d[e];
     }
+    if (rope_cos) {
+        // Rotary embedding on the unrounded row (heads of 128): the partner features i +- 64 are held by the
+        // thread 8 lanes away, which is live whenever this one is (heads never straddle N).  Every live lane
+        // takes part in the exchange; lanes of the v part keep their values.
+        float other[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) other[e] = __shfl_xor(y[e], 8);
+        if (n < Nq + Nkv) {
+            const int f0 = (n & 127), i0 = f0 & 63;
+            const int p = min(max(pos[t], 0), rope_positions - 1);
+            const f32x4 c0 = *(const f32x4 *)(rope_cos + (size_t)p * 64 + i0), c1 = *(const f32x4 *)(rope_cos + (size_t)p * 64 + i0 + 4);
+            const f32x4 s0 = *(const f32x4 *)(rope_sin + (size_t)p * 64 + i0), s1 = *(const f32x4 *)(rope_sin + (size_t)p * 64 + i0 + 4);
+            const float cc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+            const float ss[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            const float sign = f0 < 64 ? -1.f : 1.f;     // first half: y cos - partner sin; second half: y cos + partner sin
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = y[e] * cc[e] + sign * (other[e] * ss[e]);
+        }
+    }
     u32x4 out;
     {
         const f32x2 p0 = {y[0], y[1]}, p1 = {y[2], y[3]}, p2 = {y[4], y[5]}, p3 = {y[6], y[7]};
@@ -152,7 +173,7 @@ static void launch_finish(const Fwd &f, const PtrTable &B, int s_splits, const i
     const dim3 grid(f.n_blocks, (f.N + FIN_COLS - 1) / FIN_COLS);
     hipLaunchKernelGGL(finish_bf16_kernel<SPLITS>, grid, dim3(1024), 0, f.stream, (const float *)f.partial,
                        f.S, s_splits, B, f.ranks, (const bf16_t *)f.bias, f.perm, block_rows, f.blocktab, f.slot, (bf16_t *)f.q, (bf16_t *)f.kc,
-                       (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r);
+                       (bf16_t *)f.vc, f.T, f.Nq, f.Nkv, f.L, f.r, f.rope_cos, f.rope_sin, f.pos, f.rope_positions);
 }
 
 int launch_finish_bf16(const Fwd &f, const PtrTable &B, int splits, int s_splits, const int32_t *block_rows)

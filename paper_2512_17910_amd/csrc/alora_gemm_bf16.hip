@@ -70,6 +70,10 @@ struct GemmArgs {
     int prep_ranges, prep_kper;   // ranges of the hidden dimension per block-table entry, and their width
     GroupSmallArgs prep;
     void *S_out;          // shrink result written by the prep workgroups ((hi, lo) form)
+    // rotary embedding fused into the store (fused mode, 256-feature tiles, heads of 128): [rope_positions][64]
+    const float *rope_cos, *rope_sin;
+    const int32_t *pos;
+    int rope_positions;
 };
 
 // Buffer descriptor of a raw byte buffer (stride 0, 32-bit data format): offsets at or past
@@ -108,7 +112,7 @@ __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p, int pitch)
 // SPLIT: small-batch mode.  The workgroup index selects a tile and a range of K-slices; the kernel only accumulates the
 // base product over that range and stores the fp32 accumulators to g.partial[split][T][N]; adapters,
 // rounding and the q_out / cache stores are left to the finishing kernel.
-template <int NTW, bool SPLIT>
+template <int NTW, bool SPLIT, bool ROPE = false>
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B, PtrTable A)
 {
     constexpr int BN = 64 * NTW;
@@ -471,6 +475,78 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                 *(f32x4 *)(out + (size_t)t * g.N + n) = v;
             }
         }
+    } else if (ROPE) {
+        // Rotary embedding between the accumulators and the store.  NTW == 4 and heads of 128: a wavefront's
+        // 128 features are one head, so both halves of every plane (i, i + 64) pass through its strip.  The
+        // strip holds the unrounded fp32 rows (bias added); the lane that stores 8 features of a row reads
+        // them and their partners 64 features away, turns them by the row's angle and rounds once.
+        static_assert(!ROPE || NTW == 4, "a wavefront's strip must hold whole heads");
+        constexpr int EP = 128 * NTW + 16;     // strip row pitch in bytes (fp32)
+        constexpr int LPR = 4 * NTW;           // lanes per row (8 features each)
+        constexpr int RPI = 64 / LPR;          // rows per store instruction
+        lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
+        const int er = lane / LPR, ec = lane % LPR;
+        const int n = n0 + wn * 32 * NTW + ec * 8;
+        u32x2 bias4[NTW][4];
+#pragma unroll
+        for (int a = 0; a < NTW; ++a)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int nf = n0 + wn * 32 * NTW + a * 32 + 8 * gq + 4 * lh;
+                bias4[a][gq] = (u32x2){0u, 0u};
+                if (g.bias && nf < g.N) bias4[a][gq] = *(const u32x2 *)(g.bias + nf);
+            }
+        int region = -1, col = 0;
+        if (er < RPI && n < g.N) {
+            if (n < g.Nq) { region = 0; col = n; }
+            else if (n < g.Nq + g.Nkv) { region = 1; col = n - g.Nq; }
+            else { region = 2; col = n - g.Nq - g.Nkv; }
+        }
+        const int i0 = (8 * ec) & 63;                       // this lane's first plane within the head
+        const float sign = ec < LPR / 2 ? -1.f : 1.f;       // first half: y cos - partner sin; second: y cos + partner sin
+        const int pc = ec ^ (LPR / 2);                      // the lane position that holds the partner features
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int a = 0; a < NTW; ++a)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    f32x4 v = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1], acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
+                    v += (f32x4){__uint_as_float(bias4[a][gq].x << 16), __uint_as_float(bias4[a][gq].x & 0xffff0000u),
+                                 __uint_as_float(bias4[a][gq].y << 16), __uint_as_float(bias4[a][gq].y & 0xffff0000u)};
+                    *(__attribute__((address_space(3))) f32x4 *)(strip + li * EP + (a * 32 + 8 * gq + 4 * lh) * 4) = v;
+                }
+#pragma unroll
+            for (int i = 0; i < (32 + RPI - 1) / RPI; ++i) {
+                const int r = i * RPI + er;
+                const int row = wt * 128 + b * 32 + r;
+                if (region < 0 || r >= 32 || m0 + row >= g.T) continue;
+                const lds_byte *sr = strip + r * EP;
+                f32x4 y0 = *(const __attribute__((address_space(3))) f32x4 *)(sr + ec * 32);
+                f32x4 y1 = *(const __attribute__((address_space(3))) f32x4 *)(sr + ec * 32 + 16);
+                if (region != 2) {
+                    const f32x4 o0 = *(const __attribute__((address_space(3))) f32x4 *)(sr + pc * 32);
+                    const f32x4 o1 = *(const __attribute__((address_space(3))) f32x4 *)(sr + pc * 32 + 16);
+                    const int p = min(max(g.pos[m0 + row], 0), g.rope_positions - 1);
+                    const float *ct = g.rope_cos + (size_t)p * 64 + i0, *stb = g.rope_sin + (size_t)p * 64 + i0;
+                    const f32x4 c0 = *(const f32x4 *)ct, c1 = *(const f32x4 *)(ct + 4);
+                    const f32x4 s0 = *(const f32x4 *)stb, s1 = *(const f32x4 *)(stb + 4);
+                    y0 = y0 * c0 + sign * (o0 * s0);
+                    y1 = y1 * c1 + sign * (o1 * s1);
+                }
+                u32x4 v;
+                v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y0.x, y0.y}, bf16x2));
+                v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y0.z, y0.w}, bf16x2));
+                v.z = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y1.x, y1.y}, bf16x2));
+                v.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y1.z, y1.w}, bf16x2));
+                if (region == 0) {
+                    *(u32x4 *)(g.q + (size_t)(m0 + row) * g.Nq + col) = v;
+                } else {
+                    const int64_t sl = slot_lds[row];
+                    if (sl >= 0) *(u32x4 *)((region == 1 ? g.kc : g.vc) + (size_t)sl * g.Nkv + col) = v;
+                }
+            }
+        }
     } else {
         constexpr int EP = 64 * NTW + 16;      // strip row pitch in bytes
         constexpr int LPR = 4 * NTW;           // lanes per row (16 bytes each)
@@ -588,6 +664,8 @@ static void launch_ntw(const GemmArgs &g, const PtrTable &B, const PtrTable &A, 
     const dim3 block(GEMM_THREADS);
     if (g.splits > 1)
         hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, true>), dim3(g.tiles8 * g.splits + g.prep_wgs), block, 0, stream, g, B, A);
+    else if (NTW == 4 && g.rope_cos)
+        hipLaunchKernelGGL((alora_gemm_bf16_kernel<4, false, true>), dim3(g.tiles8), block, 0, stream, g, B, A);
     else
         hipLaunchKernelGGL((alora_gemm_bf16_kernel<NTW, false>), dim3(g.tiles8), block, 0, stream, g, B, A);
 }
@@ -604,7 +682,11 @@ bool prep_in_projection(const Fwd &f)
 int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEvent_t after_projection)
 {
     if (f.T == 0) return 0;
-    const GemmPlan plan = plan_gemm(f.T, f.H, f.N);
+    GemmPlan plan = plan_gemm(f.T, f.H, f.N);
+    // the fused rotary embedding wants whole heads of 128 in a wavefront's strip: 256-feature tiles (the number
+    // of splits, which the shrink's layout depends on, stays what the sizes alone give; with splits the
+    // finishing kernel rotates)
+    if (f.rope_cos && plan.splits == 1) plan.ntw = 4;
     GemmArgs g;
     g.x = (const bf16_t *)f.x; g.W = (const bf16_t *)f.W; g.S_hl = (const bf16_t *)f.S;
     g.aeff = f.aeff; g.slot = f.slot;
@@ -627,6 +709,7 @@ int launch_gemm_bf16(const Fwd &f, const PtrTable &B, const PtrTable &A, hipEven
     g.prep_wgs = prep ? f.n_blocks * g.prep_ranges : 0;
     g.prep = GroupSmallArgs{f.aid, f.seg, f.pos, f.start, f.active, f.aeff, f.perm, f.offsets, f.blocktab, f.n_blocks, f.block_rows};
     g.S_out = f.S;
+    g.rope_cos = f.rope_cos; g.rope_sin = f.rope_sin; g.pos = f.pos; g.rope_positions = f.rope_positions;
     if (plan.ntw == 4) launch_ntw<4>(g, B, A, f.stream);
     else if (plan.ntw == 3) launch_ntw<3>(g, B, A, f.stream);
     else launch_ntw<2>(g, B, A, f.stream);

@@ -32,6 +32,8 @@ struct Fwd {
     const void *x, *W;
     const void *bias;    // [N] or null: added to the base output of every row (Algorithm 1, l.apply(x, b))
     RankTable ranks;     // per adapter, <= r
+    const float *rope_cos, *rope_sin;   // [rope_positions][D / 2] or null: rotary embedding fused into the store
+    int rope_positions, D;              // D = head_dim
     const int32_t *aid, *seg, *pos, *start;
     const int64_t *slot;
     void *q, *kc, *vc;
@@ -115,5 +117,6 @@ struct ShrinkWork {
 };
 int shrink_items(int T, int L);   // entries of the work list
 ShrinkPlan plan_shrink(int T, int H, int N, int L, int r);
+int launch_rope_f32(const Fwd &f);   // fp32 path: rotation of the stored q and k rows in place
 
 }  // namespace alora
