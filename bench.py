@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--reuse-grouping", action="store_true",
                     help="not the headline step: time the per-layer call of a model whose layers share one token batch "
                          "(classification and grouping done once, before the timed region, and reused by every step)")
+    ap.add_argument("--rope", action="store_true",
+                    help="rotary embedding of q and k fused into the store (not the headline workload: the paper's path has none)")
     ap.add_argument("--library-gemm", action="store_true",
                     help="context, not part of the path: also time the vendor library's plain bf16 GEMM x @ W of the "
                          "same shape (torch.matmul: no adapters, no mask, no cache scatter) on the same box")
@@ -83,11 +85,20 @@ def main() -> int:
                                             w.block_size, db.dims, db.ws, bias=db.bias,
                                             adapter_ranks=w.adapter_ranks) for (W, A, B) in copies]
 
+    rope = None
+    if args.rope:
+        cos, sin = wl.rope_table(int(w.token_positions.max()) + 1, w.head_dim)
+        rope = (torch.from_numpy(cos).to("cuda"), torch.from_numpy(sin).to("cuda"))
+
     def step(i):
         if graphs:
             ab.alora_qkv_graph_launch(graphs[i % rotate])
             return
         W, A, B = copies[i % rotate]
+        if rope is not None:
+            ab.alora_qkv_forward_ex(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot, w.block_size, db.dims,
+                                    db.ws, bias=db.bias, adapter_ranks=w.adapter_ranks, rope=rope)
+            return
         if args.reuse_grouping:
             ab.alora_qkv_forward_ex(db.x, db.aid, db.start, W, A, B, db.q, db.kc, db.vc, db.slot, w.block_size, db.dims,
                                     db.ws, bias=db.bias, adapter_ranks=w.adapter_ranks, reuse_grouping=True)
@@ -179,7 +190,8 @@ def main() -> int:
            "config": {"workload": w.name, "T": w.T, "hidden": w.hidden, "N": w.N, "n_adapters": w.n_adapters,
                       "rank": w.rank, "active_rows": T_act, "block_size": w.block_size,
                       "weight_copies_rotated": rotate, "hip_graph": bool(graphs),
-                      "grouping_reused_from_an_earlier_call": bool(args.reuse_grouping)},
+                      "grouping_reused_from_an_earlier_call": bool(args.reuse_grouping),
+                      "rotary_embedding_fused": bool(args.rope)},
            "host_enqueue_us_per_step": (t_enq - t0) * 1e6 / args.steps,
            "step_us_median": per_step_us[len(per_step_us) // 2], "step_us_min": per_step_us[0],
            "roofline": roof}

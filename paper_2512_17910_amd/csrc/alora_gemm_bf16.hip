@@ -478,15 +478,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     } else if (ROPE) {
         // Rotary embedding between the accumulators and the store.  NTW == 4 and heads of 128: a wavefront's
         // 128 features are one head, so both halves of every plane (i, i + 64) pass through its strip.  The
-        // strip holds the unrounded fp32 rows (bias added); the lane that stores 8 features of a row reads
-        // them and their partners 64 features away, turns them by the row's angle and rounds once.
+        // strip holds the unrounded fp32 rows (bias added); a lane takes 8 planes of a row -- features
+        // 8c .. 8c+7 and the 8 that lie 64 further on, which share their angles -- turns them and rounds once.
         static_assert(!ROPE || NTW == 4, "a wavefront's strip must hold whole heads");
         constexpr int EP = 128 * NTW + 16;     // strip row pitch in bytes (fp32)
-        constexpr int LPR = 4 * NTW;           // lanes per row (8 features each)
+        constexpr int LPR = 2 * NTW;           // lanes per row (2 x 8 features each)
         constexpr int RPI = 64 / LPR;          // rows per store instruction
         lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
         const int er = lane / LPR, ec = lane % LPR;
-        const int n = n0 + wn * 32 * NTW + ec * 8;
+        const int n = n0 + wn * 32 * NTW + ec * 8;         // first of the lower 8 features; the upper 8 are n + 64
         u32x2 bias4[NTW][4];
 #pragma unroll
         for (int a = 0; a < NTW; ++a)
@@ -496,15 +496,24 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                 bias4[a][gq] = (u32x2){0u, 0u};
                 if (g.bias && nf < g.N) bias4[a][gq] = *(const u32x2 *)(g.bias + nf);
             }
-        int region = -1, col = 0;
-        if (er < RPI && n < g.N) {
+        int region = -1, col = 0;                          // the head lies in one region (N is a multiple of 128)
+        if (n < g.N) {
             if (n < g.Nq) { region = 0; col = n; }
             else if (n < g.Nq + g.Nkv) { region = 1; col = n - g.Nq; }
             else { region = 2; col = n - g.Nq - g.Nkv; }
         }
-        const int i0 = (8 * ec) & 63;                       // this lane's first plane within the head
-        const float sign = ec < LPR / 2 ? -1.f : 1.f;       // first half: y cos - partner sin; second: y cos + partner sin
-        const int pc = ec ^ (LPR / 2);                      // the lane position that holds the partner features
+        // positions of the tile's rows (clamped into the tables), kept behind the last wavefront's strip
+        int *pos_lds = (int *)(st[NST - 1] + 24 * 1024);
+        if (tid < BM) pos_lds[tid] = m0 + tid < g.T ? min(max(g.pos[m0 + tid], 0), g.rope_positions - 1) : 0;
+        __syncthreads();
+        auto angles = [&](int row, f32x4 (&cs)[4]) {      // cos and sin of the lane's 8 planes at the row's position
+            const size_t at = (size_t)pos_lds[row] * 64 + 8 * ec;
+            cs[0] = *(const f32x4 *)(g.rope_cos + at); cs[1] = *(const f32x4 *)(g.rope_cos + at + 4);
+            cs[2] = *(const f32x4 *)(g.rope_sin + at); cs[3] = *(const f32x4 *)(g.rope_sin + at + 4);
+        };
+        constexpr int ITERS = 32 / RPI;
+        f32x4 cs[4] = {}, cs_next[4] = {};
+        if (region == 0 || region == 1) angles(wt * 128 + er, cs);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
 #pragma unroll
@@ -517,34 +526,47 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                     *(__attribute__((address_space(3))) f32x4 *)(strip + li * EP + (a * 32 + 8 * gq + 4 * lh) * 4) = v;
                 }
 #pragma unroll
-            for (int i = 0; i < (32 + RPI - 1) / RPI; ++i) {
+            for (int i = 0; i < ITERS; ++i) {
                 const int r = i * RPI + er;
                 const int row = wt * 128 + b * 32 + r;
-                if (region < 0 || r >= 32 || m0 + row >= g.T) continue;
-                const lds_byte *sr = strip + r * EP;
-                f32x4 y0 = *(const __attribute__((address_space(3))) f32x4 *)(sr + ec * 32);
-                f32x4 y1 = *(const __attribute__((address_space(3))) f32x4 *)(sr + ec * 32 + 16);
-                if (region != 2) {
-                    const f32x4 o0 = *(const __attribute__((address_space(3))) f32x4 *)(sr + pc * 32);
-                    const f32x4 o1 = *(const __attribute__((address_space(3))) f32x4 *)(sr + pc * 32 + 16);
-                    const int p = min(max(g.pos[m0 + row], 0), g.rope_positions - 1);
-                    const float *ct = g.rope_cos + (size_t)p * 64 + i0, *stb = g.rope_sin + (size_t)p * 64 + i0;
-                    const f32x4 c0 = *(const f32x4 *)ct, c1 = *(const f32x4 *)(ct + 4);
-                    const f32x4 s0 = *(const f32x4 *)stb, s1 = *(const f32x4 *)(stb + 4);
-                    y0 = y0 * c0 + sign * (o0 * s0);
-                    y1 = y1 * c1 + sign * (o1 * s1);
+                // the angles of the next row this lane handles are requested before this row's stores go out
+                const int nxt = i + 1 < ITERS ? row + RPI : (b < 3 ? wt * 128 + (b + 1) * 32 + er : -1);
+                if ((region == 0 || region == 1) && nxt >= 0) angles(nxt, cs_next);
+                if (region >= 0 && m0 + row < g.T) {
+                    const lds_byte *sr = strip + r * EP;
+                    f32x4 lo0 = *(const __attribute__((address_space(3))) f32x4 *)(sr + ec * 32);
+                    f32x4 lo1 = *(const __attribute__((address_space(3))) f32x4 *)(sr + ec * 32 + 16);
+                    f32x4 hi0 = *(const __attribute__((address_space(3))) f32x4 *)(sr + 256 + ec * 32);
+                    f32x4 hi1 = *(const __attribute__((address_space(3))) f32x4 *)(sr + 256 + ec * 32 + 16);
+                    if (region != 2) {
+                        const f32x4 a0 = lo0, a1 = lo1;
+                        lo0 = a0 * cs[0] - hi0 * cs[2];
+                        lo1 = a1 * cs[1] - hi1 * cs[3];
+                        hi0 = hi0 * cs[0] + a0 * cs[2];
+                        hi1 = hi1 * cs[1] + a1 * cs[3];
+                    }
+                    u32x4 vl, vh;
+                    vl.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo0.x, lo0.y}, bf16x2));
+                    vl.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo0.z, lo0.w}, bf16x2));
+                    vl.z = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo1.x, lo1.y}, bf16x2));
+                    vl.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){lo1.z, lo1.w}, bf16x2));
+                    vh.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){hi0.x, hi0.y}, bf16x2));
+                    vh.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){hi0.z, hi0.w}, bf16x2));
+                    vh.z = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){hi1.x, hi1.y}, bf16x2));
+                    vh.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){hi1.z, hi1.w}, bf16x2));
+                    bf16_t *dst = nullptr;
+                    if (region == 0) dst = g.q + (size_t)(m0 + row) * g.Nq + col;
+                    else {
+                        const int64_t sl = slot_lds[row];
+                        if (sl >= 0) dst = (region == 1 ? g.kc : g.vc) + (size_t)sl * g.Nkv + col;
+                    }
+                    if (dst) {
+                        *(u32x4 *)dst = vl;
+                        *(u32x4 *)(dst + 64) = vh;
+                    }
                 }
-                u32x4 v;
-                v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y0.x, y0.y}, bf16x2));
-                v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y0.z, y0.w}, bf16x2));
-                v.z = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y1.x, y1.y}, bf16x2));
-                v.w = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y1.z, y1.w}, bf16x2));
-                if (region == 0) {
-                    *(u32x4 *)(g.q + (size_t)(m0 + row) * g.Nq + col) = v;
-                } else {
-                    const int64_t sl = slot_lds[row];
-                    if (sl >= 0) *(u32x4 *)((region == 1 ? g.kc : g.vc) + (size_t)sl * g.Nkv + col) = v;
-                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) cs[u] = cs_next[u];
             }
         }
     } else {

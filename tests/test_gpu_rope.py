@@ -111,3 +111,26 @@ def test_argument_checks():
     with pytest.raises(ab.AloraError) as e:
         _run(db, (dev[0], None))                        # one table without the other
     assert e.value.status == ab.ALORA_EINVAL
+
+
+def test_graph_replays_carry_the_rotation():
+    """A captured call with the tables baked in: three replays (eager work and synchronisations in between)
+    give the bits of the eager call."""
+    w = wl.small_mixed("bf16", hidden=1024, head_dim=128, seq_lens=(100, 31, 1, 64), seed=29)
+    cos, sin, dev = _tables(w)
+    db = DeviceBatch(w)
+    _run(db, dev)
+    want = (raw_bits(db.q).copy(), raw_bits(db.kc).copy(), raw_bits(db.vc).copy())
+    st = DeviceBatch(w)
+    g = ab.alora_qkv_graph_create(st.x, st.aid, st.start, st.W, st.A, st.B, st.q, st.kc, st.vc, st.slot, w.block_size,
+                                  st.dims, st.ws, rope=dev)
+    try:
+        for _ in range(3):
+            st.reset()
+            torch.cuda.synchronize()
+            ab.alora_qkv_graph_launch(g)
+            torch.cuda.synchronize()
+            assert np.array_equal(raw_bits(st.q), want[0])
+            assert np.array_equal(raw_bits(st.kc), want[1]) and np.array_equal(raw_bits(st.vc), want[2])
+    finally:
+        ab.alora_qkv_graph_destroy(g)
