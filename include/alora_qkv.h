@@ -192,7 +192,7 @@ int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const 
  * own; nothing runs) and hands back the instantiated graph; every alora_qkv_graph_launch replays
  * the whole call (classification/grouping, shrink, projection, stores) on `hip_stream`.
  *   - Arguments, layouts and preconditions are those of alora_qkv_forward_ex (extras may be NULL;
- *     the rank array is read at creation, the bias pointer is baked in); T must be > 0.
+ *     the rank array is read at creation, the bias and rotary-table pointers are baked in); T must be > 0.
  *   - All addresses are baked in: before a launch the caller rewrites the CONTENTS of x,
  *     token_adapter_ids, dims->token_seg_ids, dims->token_positions, activation_start and
  *     slot_mapping in place.  A batch with fewer than T rows is padded with rows that have
