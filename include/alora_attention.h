@@ -101,6 +101,22 @@ int alora_paged_attention_suffix(const void *q, const void *k_cache, const void 
                                  const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                                  const alora_attn_dims *dims, void *hip_stream);
 
+/*
+ * alora_paged_attention_suffix for batches with few row blocks -- the common aLoRA request: a short invocation
+ * suffix over a long cached context (Sec. 4.2) -- where one workgroup per (row block, K/V head) would leave
+ * most of the chip idle: every row block's context is cut into parts, one workgroup each (about 1024
+ * workgroups, at most 32 parts; one part when the batch has 512 or more (row block, K/V head) pairs: then
+ * this IS alora_paged_attention_suffix and the workspace may be NULL), the parts leave (running maximum,
+ * sum of weights, unnormalised output) in the workspace and a second kernel combines them in part order.
+ * Results equal those of alora_paged_attention_suffix up to fp32 summation order and do not depend on timing.
+ *   workspace  device, 16-byte aligned, >= alora_paged_attention_suffix_workspace_bytes() bytes; contents on
+ *              entry irrelevant; calls that share it must be stream-ordered.  ALORA_EWORKSPACE otherwise.
+ */
+int alora_paged_attention_suffix_workspace_bytes(const alora_attn_dims *dims, size_t *out_bytes);
+int alora_paged_attention_suffix_split(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                       const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
+                                       const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Host-side check of the index data of a call (synchronous; device pointers): every sequence id in
  * [0, n_seqs), every position in [0, max_blocks * block_size), every table entry a row's context
  * reaches in [0, n_slots / block_size).  ALORA_OK, ALORA_EDATA, or an argument error. */

@@ -36,6 +36,7 @@ def main() -> None:
     ap.add_argument("--suffix", type=int, default=0, metavar="ROWS",
                     help="4 sequences of 16384 positions whose last ROWS positions are query rows (a projected suffix over "
                          "a cached prefix), through alora_paged_attention_suffix; with --single-pass through the per-row call")
+    ap.add_argument("--split", action="store_true", help="with --suffix: through alora_paged_attention_suffix_split")
     ap.add_argument("--decode-through-suffix", action="store_true", help="the default decode batch through the suffix call")
     args = ap.parse_args()
 
@@ -89,6 +90,10 @@ def main() -> None:
     if (args.suffix and not args.single_pass) or args.decode_through_suffix:
         call = lambda: ab.alora_paged_attention_suffix(q, kc, vc, bt_d, seq_d, pos_d, out, dims)
         name += "-rowblocks"
+        if args.split:
+            ws = torch.empty(max(ab.alora_paged_attention_suffix_workspace_bytes(dims), 16), dtype=torch.uint8, device=dev)
+            call = lambda: ab.alora_paged_attention_suffix_split(q, kc, vc, bt_d, seq_d, pos_d, out, dims, ws)
+            name += "-split"
     if args.few and not args.single_pass:
         ws = torch.empty(max(ab.alora_paged_attention_workspace_bytes(dims), 16), dtype=torch.uint8, device=dev)
         call = lambda: ab.alora_paged_attention_split(q, kc, vc, bt_d, seq_d, pos_d, out, dims, ws)

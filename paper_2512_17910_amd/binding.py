@@ -83,6 +83,8 @@ def lib() -> ctypes.CDLL:
         L.alora_paged_attention_suffix.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp]
         L.alora_paged_attention_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp, sz, vp]
         L.alora_paged_attention_workspace_bytes.argtypes = [ctypes.POINTER(AloraAttnDims), ctypes.POINTER(sz)]
+        L.alora_paged_attention_suffix_split.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp, sz, vp]
+        L.alora_paged_attention_suffix_workspace_bytes.argtypes = [ctypes.POINTER(AloraAttnDims), ctypes.POINTER(sz)]
         L.alora_status_string.argtypes = [ctypes.c_int]
         L.alora_status_string.restype = ctypes.c_char_p
         L.alora_qkv_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
@@ -95,7 +97,8 @@ def lib() -> ctypes.CDLL:
                      "alora_qkv_forward", "alora_qkv_validate", "alora_last_hip_error", "alora_qkv_version",
                      "alora_qkv_forward_ex", "alora_qkv_graph_create", "alora_qkv_graph_launch", "alora_qkv_graph_destroy",
                      "alora_paged_attention", "alora_paged_attention_validate", "alora_paged_attention_split", "alora_paged_attention_suffix",
-                     "alora_paged_attention_workspace_bytes"):
+                     "alora_paged_attention_workspace_bytes", "alora_paged_attention_suffix_split",
+                     "alora_paged_attention_suffix_workspace_bytes"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -325,3 +328,22 @@ def alora_paged_attention_suffix(q, k_cache, v_cache, block_tables, token_seq_id
                                            _ptr(token_positions), _ptr(out), ctypes.byref(dims), _stream_handle(stream))
     if s:
         raise AloraError(s, "alora_paged_attention_suffix")
+
+
+def alora_paged_attention_suffix_workspace_bytes(dims: AloraAttnDims) -> int:
+    out = ctypes.c_size_t(0)
+    s = lib().alora_paged_attention_suffix_workspace_bytes(ctypes.byref(dims), ctypes.byref(out))
+    if s:
+        raise AloraError(s, "alora_paged_attention_suffix_workspace_bytes")
+    return int(out.value)
+
+
+def alora_paged_attention_suffix_split(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out,
+                                       dims: AloraAttnDims, workspace, stream=None) -> None:
+    """alora_paged_attention_suffix with every row block's context cut into parts (few row blocks, long contexts)."""
+    s = lib().alora_paged_attention_suffix_split(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                                 _ptr(token_seq_ids), _ptr(token_positions), _ptr(out), ctypes.byref(dims),
+                                                 _ptr(workspace), workspace.numel() if workspace is not None else 0,
+                                                 _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_paged_attention_suffix_split")

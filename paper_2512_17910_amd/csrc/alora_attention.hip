@@ -384,6 +384,23 @@ static int plan_splits(const alora_attn_dims *d)
     return (int)std::min<long long>(32, (1024 + wgs - 1) / wgs);
 }
 
+// The same for the row-block kernel, whose unit of work is a block of 128 / G rows: parts when the batch
+// has fewer than 512 (row block, K/V head) pairs.
+static int plan_block_splits(const alora_attn_dims *d)
+{
+    const int G = d->n_q_heads / d->n_kv_heads, rbg = 128 / G;
+    const long long wgs = (long long)((d->n_tokens + rbg - 1) / rbg) * d->n_kv_heads;
+    if (wgs <= 0 || wgs >= 512) return 1;
+    return (int)std::min<long long>(32, (1024 + wgs - 1) / wgs);
+}
+
+static size_t block_split_bytes(const alora_attn_dims *d)
+{
+    const int sp = plan_block_splits(d);
+    if (sp <= 1) return 0;
+    return (size_t)d->n_tokens * d->n_q_heads * sp * (d->head_dim + 2) * sizeof(float);
+}
+
 static size_t split_bytes(const alora_attn_dims *d)
 {
     const int sp = plan_splits(d);
@@ -425,6 +442,25 @@ int alora_paged_attention_suffix(const void *q, const void *k_cache, const void 
                       hip_stream);
 }
 
+int alora_paged_attention_suffix_workspace_bytes(const alora_attn_dims *dims, size_t *out_bytes)
+{
+    using namespace alora;
+    if (!out_bytes) return ALORA_EINVAL;
+    const int st = check_dims(dims);
+    if (st) return st;
+    if (dims->dtype != ALORA_BF16 || dims->head_dim != 128) return ALORA_ESHAPE;
+    *out_bytes = block_split_bytes(dims);
+    return ALORA_OK;
+}
+
+int alora_paged_attention_suffix_split(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
+                                       const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
+                                       const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, workspace,
+                      workspace_bytes, 3, hip_stream);
+}
+
 int alora_paged_attention(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                           const alora_attn_dims *dims, void *hip_stream)
@@ -443,9 +479,14 @@ static int run(const void *q, const void *k_cache, const void *v_cache, const in
 {
     const int st = check_dims(dims);
     if (st) return st;
-    const int splits = mode == 1 ? plan_splits(dims) : 1;
-    if (mode == 2 && (dims->dtype != ALORA_BF16 || dims->head_dim != 128)) return ALORA_ESHAPE;
-    if (splits > 1 && (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < split_bytes(dims))) return ALORA_EWORKSPACE;
+    if (mode >= 2 && (dims->dtype != ALORA_BF16 || dims->head_dim != 128)) return ALORA_ESHAPE;
+    // (the row-block kernel reads one table entry per four aligned positions; other block sizes, and a call
+    // without table or cache, take the per-row kernel)
+    const bool row_blocks = mode >= 2 && dims->block_size % 4 == 0 && dims->n_seqs >= 1 && dims->max_blocks >= 1 &&
+                            dims->n_slots >= dims->block_size;
+    const int splits = mode == 1 ? plan_splits(dims) : (mode == 3 && row_blocks) ? plan_block_splits(dims) : 1;
+    const size_t need = mode == 1 ? split_bytes(dims) : mode == 3 ? block_split_bytes(dims) : 0;
+    if (splits > 1 && (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < need)) return ALORA_EWORKSPACE;
     if (dims->n_tokens == 0) return ALORA_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !token_seq_ids || !token_positions || !out) return ALORA_EINVAL;
     if (((uintptr_t)q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15) return ALORA_EINVAL;
@@ -466,11 +507,15 @@ static int run(const void *q, const void *k_cache, const void *v_cache, const in
     a.scale_log2e = scale * 1.4426950408889634f;
     const bool bf16 = dims->dtype == ALORA_BF16;
     const int G = dims->n_q_heads / dims->n_kv_heads;
-    // (the row-block kernel reads one table entry per four aligned positions; other block sizes, and a call
-    // without table or cache, take the per-row kernel)
-    if (mode == 2 && dims->block_size % 4 == 0 && dims->n_seqs >= 1 && dims->max_blocks >= 1 && dims->n_slots >= dims->block_size) {
+    if (row_blocks) {
         const int e2 = launch_attention_blocks(a, G, (hipStream_t)hip_stream);
         if (e2) { note_hip_error(e2); return ALORA_EHIP; }
+        if (splits > 1) {
+            hipLaunchKernelGGL((paged_attention_merge_kernel<128, true>), dim3((unsigned)a.T * (unsigned)a.Hq), dim3(128), 0,
+                               (hipStream_t)hip_stream, a.part, a.out, a.splits);
+            const hipError_t e3 = hipGetLastError();
+            if (e3) { note_hip_error((int)e3); return ALORA_EHIP; }
+        }
         return ALORA_OK;
     }
     const bool launched = dims->head_dim == 128 ? launch_d<128>(a, G, bf16, (hipStream_t)hip_stream)

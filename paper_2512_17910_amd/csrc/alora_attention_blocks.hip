@@ -116,12 +116,14 @@ __global__ __launch_bounds__(512, 4) void paged_attention_blocks_kernel(AttnArgs
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, c16 = lane & 15, g4 = lane >> 4;
     const int wu = __builtin_amdgcn_readfirstlane(w);
-    const int hk = (int)blockIdx.x % a.Hkv;
+    // grid: (range of batch rows, K/V head, part of the context); a.splits parts, 1 = the whole context
+    const int part = (int)blockIdx.x % a.splits, bid = (int)blockIdx.x / a.splits;
+    const int hk = bid % a.Hkv;
     // ---- this workgroup's R batch rows (R a power of two <= 32, <= RBG) ------------------------------------
     // With R < RBG a long run of rows has a leading row in every (RBG / R)-th range only, and workgroups are
     // handed to the shader engines of an XCD in turn (four of them): without the exchange of the two low index
     // bits below, all the work of such a batch would land on one engine in four.
-    int k = (int)blockIdx.x / a.Hkv;
+    int k = bid / a.Hkv;
     {
         const int n_ranges = (a.T + R - 1) / R, mm = RBG / R;
         if (mm > 1 && (k | 3) < n_ranges) k ^= (k / mm) & (mm >= 4 ? 3 : 1);
@@ -191,7 +193,15 @@ __global__ __launch_bounds__(512, 4) void paged_attention_blocks_kernel(AttnArgs
     }
     int n_ctx = 0;
     if (row_ok) n_ctx = (int)((long long)p0 + nrows < cap ? (long long)p0 + nrows : cap);
-    const int n_chunks = (n_ctx + 31) >> 5;
+    // this workgroup's part of the context: blocks c_lo .. c_hi - 1 of 32 positions (all of them without parts)
+    int c_lo = 0, c_hi = (n_ctx + 31) >> 5;
+    if (a.splits > 1) {
+        const int per = (c_hi + a.splits - 1) / a.splits;
+        c_lo = min(part * per, c_hi);
+        c_hi = min(c_lo + per, c_hi);
+        n_ctx = min(n_ctx, 32 * c_hi);                 // positions past the part are not loaded
+    }
+    const int n_chunks = c_hi;
     const int32_t *bt = a.bt + (size_t)(row_ok ? sq : 0) * a.max_blocks;
 
     // this lane's column: query row r_j of the block (rows w*RBW .. of this wavefront), query head g_j
@@ -224,8 +234,9 @@ __global__ __launch_bounds__(512, 4) void paged_attention_blocks_kernel(AttnArgs
     // by the whole workgroup when the lookups reach its end (the index of four aligned positions is the same
     // in every lane); an entry past the context reads as -1.
     auto entry_of = [&](int pu) { return POW2 ? (pu >> a.bs_shift) : (pu / a.bs); };
-    int win_first = 0;                       // table index of window[0]
+    int win_first = 0, win_block = 0;        // table index of window[0]; first block the window covers
     auto refill = [&](int cw) {              // entries of blocks cw .. cw + WIN - 1; all wavefronts call it together
+        win_block = cw;
         win_first = entry_of(32 * cw);
         const int last = entry_of(min(32 * (cw + WIN), n_ctx) - 1);      // n_ctx > 32 * cw whenever this is called
         __syncthreads();
@@ -324,20 +335,20 @@ __global__ __launch_bounds__(512, 4) void paged_attention_blocks_kernel(AttnArgs
     // block c+3, whose table entry was looked up a step earlier.  Blocks past the context are copied too (all
     // zeros, from one 16-byte constant), which keeps the count of copies in flight the same in every step.
     {
-        if (n_chunks > 0) refill(0);
+        if (n_chunks > c_lo) refill(c_lo);
 #pragma unroll
-        for (int kk = 0; kk < NB - 1; ++kk) issue(kk, lookup(32 * kk));
-        int b0 = lookup(32 * (NB - 1));
+        for (int kk = 0; kk < NB - 1; ++kk) issue(c_lo + kk, lookup(32 * (c_lo + kk)));
+        int b0 = lookup(32 * (c_lo + NB - 1));
         auto step = [&](int c) {
             asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
             issue(c + NB - 1, b0);
             const int cn = c + NB;
-            if ((cn & (WIN - 1)) == 0 && 32 * cn < n_ctx) refill(cn);
+            if (cn == win_block + WIN && 32 * cn < n_ctx) refill(cn);
             b0 = lookup(32 * cn);
         };
         // (two loops: the accumulators live in the first only)
-        const int n_chunks_w = lim_w >= 0 ? (lim_w >> 5) + 1 : 0;
-        int c = 0;
+        const int n_chunks_w = lim_w >= 0 ? min((lim_w >> 5) + 1, n_chunks) : 0;
+        int c = c_lo;
         for (; c < n_chunks_w; ++c) {
             step(c);
             consume(c);
@@ -349,6 +360,20 @@ __global__ __launch_bounds__(512, 4) void paged_attention_blocks_kernel(AttnArgs
 
     // ---- the four lanes of a column add their weight sums; normalise and store ---------------------
     l = sum_over_column(l);
+    if (a.splits > 1) {
+        // this part's (running maximum, weight sum, unnormalised output) of every column, for the kernel that
+        // combines the parts of a (row, query head) in part order
+        if (col_ok || (!row_ok && w == 0 && c16 < G)) {
+            float *pp = a.part + (((size_t)(t0 + (col_ok ? r_j : 0)) * a.Hq + (size_t)hk * G + g_j) * a.splits + part) * (D + 2);
+            if (g4 == 0) *(f32x2 *)pp = (f32x2){m, l};
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                *(f32x2 *)(pp + 2 + 16 * t + 4 * g4) = (f32x2){acc[t][0], acc[t][1]};
+                *(f32x2 *)(pp + 2 + 16 * t + 4 * g4 + 2) = (f32x2){acc[t][2], acc[t][3]};
+            }
+        }
+        continue;
+    }
     // a row that is not valid leads a block of its own and gets zeros
     if (col_ok || (!row_ok && w == 0 && c16 < G)) {
         const float inv = l > 0.f ? 1.f / l : 0.f;
@@ -366,9 +391,10 @@ int launch_attention_blocks(const AttnArgs &a, int G, hipStream_t stream)
 {
     // batch rows per workgroup: a whole row block where that still makes a few workgroups per CU, fewer for
     // small batches (a decode batch: every row leads a block of its own)
-    int R = 32 / G * 4 < 32 ? 32 / G * 4 : 32;
-    while (R > 1 && (long long)((a.T + R - 1) / R) * a.Hkv < 2048) R /= 2;
-    const dim3 grid((unsigned)((a.T + R - 1) / R) * (unsigned)a.Hkv), block(512);
+    int R = 128 / G < 32 ? 128 / G : 32;
+    // (with the context cut into parts the batch is small: whole row blocks per workgroup, the parts fill the chip)
+    while (a.splits == 1 && R > 1 && (long long)((a.T + R - 1) / R) * a.Hkv < 2048) R /= 2;
+    const dim3 grid((unsigned)((a.T + R - 1) / R) * (unsigned)a.Hkv * (unsigned)a.splits), block(512);
     const bool pow2 = a.bs_shift >= 0;
 #define AB_LAUNCH(GG) \
     if (pow2) hipLaunchKernelGGL((paged_attention_blocks_kernel<GG, true>), grid, block, 0, stream, a, R); \

@@ -313,6 +313,48 @@ def test_suffix_call_at_benchmark_size_on_sampled_rows():
     assert maxnorm_rel(out[rows], d.oracle(rows=rows)) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("group", [1, 4, 8])
+def test_suffix_split_cuts_the_context_of_few_row_blocks_into_parts(group):
+    """Short suffixes over long contexts (the shape of an aLoRA request): few row blocks, so every block's
+    context is cut into parts that a second kernel combines.  Contexts shorter than one part, on part
+    boundaries, across several table windows (more than 2048 positions per part); against the oracle, against
+    the unsplit call (to summation order), and two calls give the same bits."""
+    lens = [5000, 37, 2048 * 3 + 17, 64, 9000, 1]
+    rows = [16, 5, 33, 1, 40, 1]
+    c = wl.attention_case(f"suffix-split-g{group}", "bf16", lens, rows, 2 * group, 2, 128, 16, seed=wl.SEED ^ (500 + group))
+    d = DeviceCase(c)
+    nbytes = ab.alora_paged_attention_suffix_workspace_bytes(d.dims)
+    assert nbytes > 0
+    ws = torch.full((nbytes,), 0xff, dtype=torch.uint8, device="cuda")      # NaN patterns: every entry read is written first
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_suffix_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws)
+    torch.cuda.synchronize()
+    got = to_f64(d.out)
+    bits = raw_bits(d.out).copy()
+    assert np.isfinite(got).all()
+    assert maxnorm_rel(got, d.oracle()) <= TOL["bf16"]
+    assert maxnorm_rel(got, to_f64(_run_suffix(d))) <= 2.0 ** -7
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_suffix_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_bits(d.out), bits)
+    # too small a workspace is refused
+    with pytest.raises(ab.AloraError) as e:
+        ab.alora_paged_attention_suffix_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws[:nbytes // 2])
+    assert e.value.status == ab.ALORA_EWORKSPACE
+
+
+def test_suffix_split_on_a_large_batch_is_the_unsplit_call():
+    c = _mixed_batch(91, 8, 8, 8300)
+    d = DeviceCase(c)
+    assert ab.alora_paged_attention_suffix_workspace_bytes(d.dims) == 0
+    first = raw_bits(_run_suffix(d)).copy()
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_suffix_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_bits(d.out), first)
+
+
 def test_suffix_call_gives_the_same_bits_on_every_call():
     """The row-block kernel takes no timing-dependent decision: 200 calls on one batch (blocks that need no
     mask, diagonal blocks, single rows), every one bit-identical to the first."""
