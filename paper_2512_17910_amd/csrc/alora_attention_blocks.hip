@@ -11,6 +11,9 @@
 // start in it; the range index is permuted so that the leading rows of a long run do not all fall to the
 // same shader engine.
 //
+// For batches with few row blocks the context of every block is cut into parts, one workgroup each, which
+// leave (running maximum, weight sum, unnormalised output) per column for the kernel that combines them.
+//
 // Per 32 context positions a wavefront runs two sets of 16x16x32 MFMAs that keep every column in the same
 // four lanes (c, c+16, c+32, c+48) from the scores to the output:
 //   scores^T [position x column] = K [position x d] . Q^T [d x column]   two tiles of 16 positions; K rows
