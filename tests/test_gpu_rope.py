@@ -134,3 +134,35 @@ def test_graph_replays_carry_the_rotation():
             assert np.array_equal(raw_bits(st.kc), want[1]) and np.array_equal(raw_bits(st.vc), want[2])
     finally:
         ab.alora_qkv_graph_destroy(g)
+
+
+@pytest.mark.parametrize("cfg,n_sample", [(2, 64), (3, 128)])
+def test_rotation_at_benchmark_size_on_sampled_rows(cfg, n_sample):
+    """Configurations 2 (fused projection kernel) and 3 (split projection + finishing kernel) with the tables,
+    in the launch configuration bench.py --rope times: sampled rows (activation boundaries +-2, segment ends,
+    spread rows) against the oracle, and the pre-activation rows against a base-only call."""
+    w = wl.CONFIGS[cfg]()
+    print(f"[case] config {cfg} with rotation: T={w.T}", flush=True)
+    cos, sin, dev = _tables(w, slack=0)
+    db = DeviceBatch(w, cache_fill=False)
+    _run(db, dev)
+    _, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+    rows = wl.sample_rows(w, n_sample)
+    x, W, A, B = host_operands(w)
+    y = oracle.alora_rows(x, W, A, B, w.token_adapter_ids, act, rows)
+    del x, W
+    y = orope.rope_rows(y, w.token_positions[rows], cos, sin, w.n_q_heads, w.n_kv_heads, w.head_dim)
+    ridx = torch.from_numpy(rows.astype(np.int64)).to("cuda")
+    tol = TOL[w.dtype]
+    assert maxnorm_rel(to_f64(db.q[ridx]), y[:, : w.Nq]) <= tol
+    sl = w.slot_mapping[rows]
+    has = sl >= 0
+    sidx = torch.from_numpy(sl[has]).to("cuda")
+    assert maxnorm_rel(to_f64(db.kc[sidx]), y[has][:, w.Nq: w.Nq + w.Nkv]) <= tol
+    assert maxnorm_rel(to_f64(db.vc[sidx]), y[has][:, w.Nq + w.Nkv:]) <= tol
+    q1, k1 = db.q.clone(), db.kc.clone()
+    _run(db, dev, aid=torch.full_like(db.aid, -1))
+    pre_rows = torch.from_numpy(np.nonzero(act == 0)[0]).to("cuda")
+    assert torch.equal(db.q[pre_rows].view(torch.int16), q1[pre_rows].view(torch.int16))
+    pre_slots = torch.from_numpy(w.slot_mapping[(act == 0) & (w.slot_mapping >= 0)]).to("cuda")
+    assert torch.equal(db.kc[pre_slots].view(torch.int16), k1[pre_slots].view(torch.int16))
