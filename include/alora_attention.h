@@ -104,7 +104,7 @@ int alora_paged_attention_suffix(const void *q, const void *k_cache, const void 
 /*
  * alora_paged_attention_suffix for batches with few row blocks -- the common aLoRA request: a short invocation
  * suffix over a long cached context (Sec. 4.2) -- where one workgroup per (row block, K/V head) would leave
- * most of the chip idle: every row block's context is cut into parts, one workgroup each (about 1024
+ * most of the chip idle: every row block's context is cut into parts, one workgroup each (about 512
  * workgroups, at most 32 parts; one part when the batch has 512 or more (row block, K/V head) pairs: then
  * this IS alora_paged_attention_suffix and the workspace may be NULL), the parts leave (running maximum,
  * sum of weights, unnormalised output) in the workspace and a second kernel combines them in part order.

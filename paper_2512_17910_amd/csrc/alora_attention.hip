@@ -391,7 +391,7 @@ static int plan_block_splits(const alora_attn_dims *d)
     const int G = d->n_q_heads / d->n_kv_heads, rbg = 128 / G;
     const long long wgs = (long long)((d->n_tokens + rbg - 1) / rbg) * d->n_kv_heads;
     if (wgs <= 0 || wgs >= 512) return 1;
-    return (int)std::min<long long>(32, (1024 + wgs - 1) / wgs);
+    return (int)std::min<long long>(32, (512 + wgs - 1) / wgs);
 }
 
 static size_t block_split_bytes(const alora_attn_dims *d)
