@@ -408,9 +408,12 @@ static size_t split_bytes(const alora_attn_dims *d)
     return (size_t)d->n_tokens * d->n_q_heads * sp * (d->head_dim + 2) * sizeof(float);
 }
 
+// which kernel an entry point asks for
+enum Reader { PER_ROW, PER_ROW_SPLIT, ROW_BLOCKS, ROW_BLOCKS_SPLIT };
+
 static int run(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                const int32_t *token_seq_ids, const int32_t *token_positions, void *out, const alora_attn_dims *dims,
-               void *workspace, size_t workspace_bytes, int mode, void *hip_stream);
+               void *workspace, size_t workspace_bytes, Reader mode, void *hip_stream);
 
 }  // namespace alora
 
@@ -431,15 +434,15 @@ int alora_paged_attention_split(const void *q, const void *k_cache, const void *
                                 const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, workspace,
-                      workspace_bytes, 1, hip_stream);
+                      workspace_bytes, alora::PER_ROW_SPLIT, hip_stream);
 }
 
 int alora_paged_attention_suffix(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                                  const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                                  const alora_attn_dims *dims, void *hip_stream)
 {
-    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0, 2,
-                      hip_stream);
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0,
+                      alora::ROW_BLOCKS, hip_stream);
 }
 
 int alora_paged_attention_suffix_workspace_bytes(const alora_attn_dims *dims, size_t *out_bytes)
@@ -458,15 +461,15 @@ int alora_paged_attention_suffix_split(const void *q, const void *k_cache, const
                                        const alora_attn_dims *dims, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, workspace,
-                      workspace_bytes, 3, hip_stream);
+                      workspace_bytes, alora::ROW_BLOCKS_SPLIT, hip_stream);
 }
 
 int alora_paged_attention(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                           const int32_t *token_seq_ids, const int32_t *token_positions, void *out,
                           const alora_attn_dims *dims, void *hip_stream)
 {
-    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0, 0,
-                      hip_stream);
+    return alora::run(q, k_cache, v_cache, block_tables, token_seq_ids, token_positions, out, dims, nullptr, 0,
+                      alora::PER_ROW, hip_stream);
 }
 
 }  // extern "C"
@@ -475,17 +478,18 @@ namespace alora {
 
 static int run(const void *q, const void *k_cache, const void *v_cache, const int32_t *block_tables,
                const int32_t *token_seq_ids, const int32_t *token_positions, void *out, const alora_attn_dims *dims,
-               void *workspace, size_t workspace_bytes, int mode, void *hip_stream)
+               void *workspace, size_t workspace_bytes, Reader mode, void *hip_stream)
 {
     const int st = check_dims(dims);
     if (st) return st;
-    if (mode >= 2 && (dims->dtype != ALORA_BF16 || dims->head_dim != 128)) return ALORA_ESHAPE;
+    const bool blocks_asked = mode == ROW_BLOCKS || mode == ROW_BLOCKS_SPLIT;
+    if (blocks_asked && (dims->dtype != ALORA_BF16 || dims->head_dim != 128)) return ALORA_ESHAPE;
     // (the row-block kernel reads one table entry per four aligned positions; other block sizes, and a call
     // without table or cache, take the per-row kernel)
-    const bool row_blocks = mode >= 2 && dims->block_size % 4 == 0 && dims->n_seqs >= 1 && dims->max_blocks >= 1 &&
+    const bool row_blocks = blocks_asked && dims->block_size % 4 == 0 && dims->n_seqs >= 1 && dims->max_blocks >= 1 &&
                             dims->n_slots >= dims->block_size;
-    const int splits = mode == 1 ? plan_splits(dims) : (mode == 3 && row_blocks) ? plan_block_splits(dims) : 1;
-    const size_t need = mode == 1 ? split_bytes(dims) : mode == 3 ? block_split_bytes(dims) : 0;
+    const int splits = mode == PER_ROW_SPLIT ? plan_splits(dims) : (mode == ROW_BLOCKS_SPLIT && row_blocks) ? plan_block_splits(dims) : 1;
+    const size_t need = mode == PER_ROW_SPLIT ? split_bytes(dims) : mode == ROW_BLOCKS_SPLIT ? block_split_bytes(dims) : 0;
     if (splits > 1 && (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < need)) return ALORA_EWORKSPACE;
     if (dims->n_tokens == 0) return ALORA_OK;
     if (!q || !k_cache || !v_cache || !block_tables || !token_seq_ids || !token_positions || !out) return ALORA_EINVAL;
