@@ -355,6 +355,33 @@ def test_suffix_split_on_a_large_batch_is_the_unsplit_call():
     assert np.array_equal(raw_bits(d.out), first)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_suffix_calls_on_random_batches_agree_with_the_oracle_and_the_per_row_kernel(seed):
+    """Random mixes of decode rows and runs, group sizes 1..8, block sizes that are powers of two, multiples of
+    four that are not (12, 20, 24: divisions instead of shifts) and neither (6: served by the per-row kernel),
+    contexts up to a few thousand positions; the unsplit and the split call."""
+    rng = np.random.default_rng(1000 + seed)
+    group = int(rng.choice([1, 2, 4, 8]))
+    bs = int(rng.choice([4, 8, 16, 32, 64, 12, 20, 24, 6]))
+    n_seq = int(rng.integers(1, 9))
+    rows = [int(rng.choice([1, 1, int(rng.integers(2, 150))])) for _ in range(n_seq)]
+    lens = [r + int(rng.integers(0, 2600)) for r in rows]
+    c = wl.attention_case(f"suffix-random-{seed}", "bf16", lens, rows, 2 * group, 2, 128, bs, seed=wl.SEED ^ (900 + seed))
+    print(f"[case] {c.name} G={group} bs={bs} rows={rows} lens={lens}", flush=True)
+    d = DeviceCase(c)
+    want = d.oracle()
+    per_row = to_f64(d.run()).copy()
+    assert maxnorm_rel(per_row, want) <= TOL["bf16"]
+    got = to_f64(_run_suffix(d))
+    assert np.isfinite(got).all() and maxnorm_rel(got, want) <= TOL["bf16"]
+    ws = torch.full((max(ab.alora_paged_attention_suffix_workspace_bytes(d.dims), 16),), 0xff, dtype=torch.uint8, device="cuda")
+    d.out.fill_(float("nan"))
+    ab.alora_paged_attention_suffix_split(d.q, d.kc, d.vc, d.bt, d.seq, d.pos, d.out, d.dims, ws)
+    torch.cuda.synchronize()
+    got = to_f64(d.out)
+    assert np.isfinite(got).all() and maxnorm_rel(got, want) <= TOL["bf16"]
+
+
 def test_suffix_call_gives_the_same_bits_on_every_call():
     """The row-block kernel takes no timing-dependent decision: 200 calls on one batch (blocks that need no
     mask, diagonal blocks, single rows), every one bit-identical to the first."""
