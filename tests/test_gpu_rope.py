@@ -166,3 +166,21 @@ def test_rotation_at_benchmark_size_on_sampled_rows(cfg, n_sample):
     assert torch.equal(db.q[pre_rows].view(torch.int16), q1[pre_rows].view(torch.int16))
     pre_slots = torch.from_numpy(w.slot_mapping[(act == 0) & (w.slot_mapping >= 0)]).to("cuda")
     assert torch.equal(db.kc[pre_slots].view(torch.int16), k1[pre_slots].view(torch.int16))
+
+
+@pytest.mark.parametrize("tuning", [(0, 1), (0, 2)])
+def test_repeated_calls_give_the_same_bits(tuning):
+    """Fifty calls of the fused kernel (and of the split path with its finishing kernel): no timing-dependent bit."""
+    w = wl.small_mixed("bf16", hidden=1024, head_dim=128, seq_lens=(150, 37, 1, 90, 300), seed=31)
+    cos, sin, dev = _tables(w)
+    ab.alora_qkv_set_tuning(*tuning)
+    try:
+        db = DeviceBatch(w)
+        _run(db, dev)
+        first = (raw_bits(db.q).copy(), raw_bits(db.kc).copy(), raw_bits(db.vc).copy())
+        for it in range(50):
+            _run(db, dev)
+            assert np.array_equal(raw_bits(db.q), first[0]), it
+            assert np.array_equal(raw_bits(db.kc), first[1]) and np.array_equal(raw_bits(db.vc), first[2]), it
+    finally:
+        ab.alora_qkv_set_tuning(0, 0)
