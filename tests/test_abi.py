@@ -142,3 +142,11 @@ def test_paged_attention_argument_checks_answer_on_the_host():
     assert L.alora_paged_attention(*good, None, None) == ab.ALORA_EINVAL
     assert L.alora_paged_attention_validate(p(0x4000), p(0x5000), p(0x6000), ctypes.byref(_attn_dims(head_dim=32))) == ab.ALORA_ESHAPE
     assert ctypes.sizeof(ab.AloraAttnDims) == 48
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build shows one GPU's share: asking bench.py for more exits with a message before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
