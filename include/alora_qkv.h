@@ -69,6 +69,8 @@ extern "C" {
 #define ALORA_EHIP (-4)        /* a HIP call failed; see alora_last_hip_error()            */
 #define ALORA_EDATA (-5)       /* alora_qkv_validate found a violated data precondition    */
 #define ALORA_ENOMEM (-6)      /* a host-side allocation failed (validate calls, planner)   */
+/* (-7 is ALORA_ENOBLOCKS of alora_planner.h) */
+#define ALORA_ETOOBIG (-8)     /* alora_qkv_forward_static: the call needs more scratch than the static array holds */
 
 /* Sizes of one call plus the two per-token index arrays of App. B. */
 typedef struct alora_dims {
@@ -183,6 +185,33 @@ int alora_qkv_forward_ex(const void *x, const int32_t *token_adapter_ids, const 
                          const int64_t *slot_mapping, int32_t block_size,
                          const alora_dims *dims, const alora_extras *extras,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The call for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  alora_qkv_forward_ex without the workspace arguments: the
+ * workspace is a device array of ALORA_STATIC_SCRATCH_BYTES that is part of the library's code
+ * object (every GPU the library is used on holds one copy until the process ends).  The call
+ * itself calls no hipMalloc / hipFree and no allocating library routine; the caller still passes
+ * every input and output.
+ *   - Arguments, results, layouts and preconditions are those of alora_qkv_forward_ex (extras may
+ *     be NULL), except extras->reuse_grouping, which is refused (ALORA_EINVAL): the array is
+ *     shared by every call on the device, so "the grouping an earlier call left" is not the
+ *     caller's to rely on.  Results are bit-identical to alora_qkv_forward_ex.
+ *   - Limit: calls whose alora_qkv_workspace_bytes() exceeds ALORA_STATIC_SCRATCH_BYTES return
+ *     ALORA_ETOOBIG before anything is enqueued.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (no
+ *     kernel relies on them: whatever must start at zero is cleared by the call itself).  Calls on
+ *     one GPU must therefore be stream-ordered; calls that overlap on one GPU race.
+ *   - The device address of the array is looked up on the first call on each device (with that
+ *     device current), under a lock; later calls only read it.
+ */
+#define ALORA_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+size_t alora_qkv_static_scratch_bytes(void);
+int alora_qkv_forward_static(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                             const void *W_qkv, const void *const *A, const void *const *B,
+                             void *q_out, void *k_cache, void *v_cache,
+                             const int64_t *slot_mapping, int32_t block_size,
+                             const alora_dims *dims, const alora_extras *extras, void *hip_stream);
 
 /*
  * Graph-captured call.  Sec. 3 keeps the activation mask in a tensor of fixed address so that the

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("ALORA_QKV_LIB") or os.path.join(HERE, "libalora_qkv.s
 
 ALORA_F32, ALORA_BF16 = 0, 1
 ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_EWORKSPACE, ALORA_EHIP, ALORA_EDATA, ALORA_ENOMEM = 0, -1, -2, -3, -4, -5, -6
+ALORA_ETOOBIG = -8
 ALORA_MAX_ADAPTERS, ALORA_MAX_RANK = 128, 64
 
 
@@ -76,6 +77,11 @@ def lib() -> ctypes.CDLL:
         L.alora_qkv_graph_create.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                              ctypes.POINTER(AloraDims), ctypes.POINTER(AloraExtras), vp, sz,
                                              ctypes.POINTER(vp)]
+        L.alora_qkv_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                               ctypes.POINTER(AloraDims), ctypes.POINTER(AloraExtras), vp]
+        L.alora_qkv_forward_static.restype = ctypes.c_int
+        L.alora_qkv_static_scratch_bytes.argtypes = []
+        L.alora_qkv_static_scratch_bytes.restype = sz
         L.alora_qkv_graph_launch.argtypes = [vp, vp]
         L.alora_qkv_graph_destroy.argtypes = [vp]
         L.alora_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(AloraAttnDims), vp]
@@ -215,6 +221,29 @@ def alora_qkv_forward_ex(x, token_adapter_ids, activation_start, W_qkv, A: Seque
                                    _stream_handle(stream))
     if s:
         raise AloraError(s, "alora_qkv_forward_ex")
+
+
+def alora_qkv_forward_static(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,
+                             q_out, k_cache, v_cache, slot_mapping, block_size: int, dims: AloraDims,
+                             bias=None, adapter_ranks=None, stream=None, rope=None) -> None:
+    """alora_qkv_forward_ex on the library's static device scratch: no workspace argument, no allocation."""
+    ex = AloraExtras(_ptr(bias), None, 0, None, None, 0)
+    if rope is not None:
+        ex.rope_cos, ex.rope_sin, ex.rope_positions = _ptr(rope[0]), _ptr(rope[1]), int(rope[0].shape[0])
+    keep = None
+    if adapter_ranks is not None:
+        keep = (ctypes.c_int32 * len(adapter_ranks))(*[int(r) for r in adapter_ranks])
+        ex.adapter_ranks = ctypes.cast(keep, ctypes.c_void_p)
+    s = lib().alora_qkv_forward_static(_ptr(x), _ptr(token_adapter_ids), _ptr(activation_start), _ptr(W_qkv),
+                                       _ptr_array(A), _ptr_array(B), _ptr(q_out), _ptr(k_cache), _ptr(v_cache),
+                                       _ptr(slot_mapping), block_size, ctypes.byref(dims), ctypes.byref(ex),
+                                       _stream_handle(stream))
+    if s:
+        raise AloraError(s, "alora_qkv_forward_static")
+
+
+def alora_qkv_static_scratch_bytes() -> int:
+    return int(lib().alora_qkv_static_scratch_bytes())
 
 
 def alora_qkv_graph_create(x, token_adapter_ids, activation_start, W_qkv, A: Sequence, B: Sequence,

@@ -3,7 +3,9 @@
 #include <new>
 #include <vector>
 #include <algorithm>
+#include <mutex>
 #include "alora_internal.h"
+#include "alora_planner.h"
 
 namespace alora {
 
@@ -110,6 +112,39 @@ static void fill_common(Fwd &f, const alora_dims *d, const Layout &l, void *ws, 
 
 }  // namespace alora
 
+// ---- the entry point that allocates nothing ------------------------------------------------------
+// The workspace of the call is a file-scope device array: every GPU the library runs on holds its own
+// copy, at its own address, until the process ends.  Host code never uses the array's name as an
+// address; it asks the runtime for the device address once per device and passes that on.
+// (No "used" attribute on it: the compiler gives a static device variable that host code names
+// external visibility in the code object, which is how the runtime finds it by name; marked "used"
+// it stays a local symbol and the look-up fails.)
+static __device__ __align__(256) unsigned char scratch[ALORA_STATIC_SCRATCH_BYTES];
+
+namespace alora {
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+static int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+    if (dev < 0 || dev >= MAX_DEVICES) return ALORA_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e || !p) { g_last_hip_error = (int)e; return ALORA_EHIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ALORA_OK;
+}
+}  // namespace alora
+
 using namespace alora;
 
 extern "C" {
@@ -128,7 +163,8 @@ const char *alora_status_string(int s)
     case ALORA_EHIP: return "a HIP call failed (see alora_last_hip_error)";
     case ALORA_EDATA: return "device data violates a documented precondition";
     case ALORA_ENOMEM: return "a host-side allocation failed";
-    case -7: return "not enough free cache blocks (planner)";
+    case ALORA_ETOOBIG: return "the call needs more scratch than the static device array holds (alora_qkv_forward_static)";
+    case ALORA_ENOBLOCKS: return "not enough free cache blocks (planner)";
     default: return "unknown status";
     }
 }
@@ -340,6 +376,25 @@ int alora_qkv_graph_destroy(alora_graph *graph)
     delete graph;
     if (e) { g_last_hip_error = (int)e; return ALORA_EHIP; }
     return ALORA_OK;
+}
+
+size_t alora_qkv_static_scratch_bytes(void) { return ALORA_STATIC_SCRATCH_BYTES; }
+
+int alora_qkv_forward_static(const void *x, const int32_t *token_adapter_ids, const int32_t *activation_start,
+                             const void *W_qkv, const void *const *A, const void *const *B, void *q_out, void *k_cache,
+                             void *v_cache, const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims,
+                             const alora_extras *extras, void *hip_stream)
+{
+    int s = check_dims(dims);
+    if (s) return s;
+    if (make_layout(dims).total > ALORA_STATIC_SCRATCH_BYTES) return ALORA_ETOOBIG;
+    // a grouping left by "an earlier call" could be any caller's: every call on a device shares the array
+    if (extras && extras->reuse_grouping) return ALORA_EINVAL;
+    void *ws = nullptr;
+    s = static_scratch(&ws);
+    if (s) return s;
+    return forward_on(x, token_adapter_ids, activation_start, W_qkv, A, B, q_out, k_cache, v_cache, slot_mapping,
+                      block_size, dims, ws, ALORA_STATIC_SCRATCH_BYTES, hip_stream, false, extras);
 }
 
 int alora_qkv_set_tuning(int feature_tiles, int splits)
