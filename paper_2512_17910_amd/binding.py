@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_17910_amd.build` "
                               "(there is no non-HIP fallback)")
+        # torch first: its HIP runtime must be the one this process uses (a library loaded before it would
+        # bring the system's copy of the runtime in beside torch's, and the two do not share devices)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         L.alora_qkv_workspace_bytes.argtypes = [ctypes.POINTER(AloraDims), ctypes.POINTER(sz)]
