@@ -30,8 +30,10 @@
  *     slot s is offset s % block_size of physical block s / block_size (Sec. 2.4).
  *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream); calls return
  *     without synchronising.  Calls that share a workspace must be stream-ordered.
- *   - Return value: ALORA_OK or a negative status.  On any error nothing has been enqueued
- *     and no device memory has been written.
+ *   - Return value: ALORA_OK or a negative status.  On ALORA_EINVAL, ALORA_ESHAPE, ALORA_EWORKSPACE and
+ *     ALORA_ETOOBIG nothing has been enqueued and no device memory has been written (all argument
+ *     checks come before the first launch).  After ALORA_EHIP (a launch failed part-way through the
+ *     call's kernel sequence) the outputs and the workspace are undefined.
  *
  * Shape limits (ALORA_ESHAPE otherwise)
  *   bf16: hidden % 64 == 0; Nq % 8 == 0; Nkv % 8 == 0; rank in {8,16,24,...,64};
@@ -169,7 +171,10 @@ int alora_qkv_forward(const void *x, const int32_t *token_adapter_ids, const int
  *                  does not know the tables).  bf16 path: head_dim 128 only (ALORA_ESHAPE otherwise);
  *                  fp32 path: any even head_dim.
  * Per-module factors (separate A^Q, A^K, A^V with B^Q, B^K, B^V; Sec. 2.3) are the block-structured
- * special case: A = [A^Q | A^K | A^V] of rank 3r and B with B^Q, B^K, B^V on its block diagonal.
+ * special case: A = [A^Q | A^K | A^V] of rank 3r and B with B^Q, B^K, B^V on its block diagonal (zeros
+ * elsewhere).  The combined rank 3r obeys the limits above, so the rank per module is at most
+ * ALORA_MAX_RANK / 3 = 21 (bf16: 8 or 16, since 3r must be a multiple of 8), and the expand spends
+ * three times the flops of a native per-module layout on the zero blocks.
  */
 typedef struct alora_extras {
     const void *bias;

@@ -142,6 +142,14 @@ def alora_rows_var(x, W, A, B, aid, active, rows, bias=None) -> np.ndarray:
     return y
 
 
+def alora_rows_per_module(x, W_mod, A_mod, B_mod, aid, active, rows) -> np.ndarray:
+    """Sec. 2.3 as it is written: one block equation per module.  W_mod = (W^Q, W^K, W^V); A_mod[m][i] is
+    adapter i's factor [H, r] of module m and B_mod[m][i] its factor [r, N_m].  Each module is projected on
+    its own (three calls of the single-module routine); the result is [Q | K | V] per row."""
+    assert len(W_mod) == len(A_mod) == len(B_mod) == 3
+    return np.concatenate([alora_rows(x, W_mod[m], A_mod[m], B_mod[m], aid, active, rows) for m in range(3)], axis=1)
+
+
 def blend_rows(x, W, A, B, aid, paper_mask, rows) -> np.ndarray:
     """Algorithm 1 taken literally (clone, add_adapter, blend with the mask)."""
     x, W, rows, aid = _f64(x), _f64(W), _i32(rows), _i32(aid)

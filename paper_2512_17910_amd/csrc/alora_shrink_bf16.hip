@@ -30,9 +30,6 @@
 namespace alora {
 
 
-__device__ __attribute__((aligned(256))) uint32_t g_zero_page[64];  // zero-initialised
-
-
 // KSL: hidden-dimension chunk per LDS buffer; NT: 32-wide rank tiles (1 for rank <= 32, else 2)
 // WORK_LIST: walk the (block, range) items of the grouping step and combine the ranges of a block
 // here; otherwise walk the block table with blockIdx.y as the range.

@@ -201,6 +201,34 @@ def with_variants(w: Workload, ranks: Optional[Sequence[int]] = None, bias: bool
     return v
 
 
+def with_per_module_factors(w: Workload, seed: int = SEED):
+    """Sec. 2.3 gives every module its own low-rank update (Delta^Q, Delta^K, Delta^V).  Draws separate
+    factors A^m_i [hidden, r], B^m_i [r, N_m] with r = w.rank / 3 for m in (Q, K, V) and returns
+    (v, A_mod, B_mod): v is the same batch whose fused factors are the block-structured encoding
+    A_i = [A^Q_i | A^K_i | A^V_i], B_i = blockdiag(B^Q_i, B^K_i, B^V_i); A_mod[m][i], B_mod[m][i] are the
+    module factors in the storage dtype.  Layout only: no arithmetic of the method."""
+    import copy
+    assert w.rank % 3 == 0
+    r = w.rank // 3
+    widths = (w.Nq, w.Nkv, w.Nkv)
+    A_mod = [[_normal(seed ^ 0x3D, _ST_A, 16 * i + m, (w.hidden, r), w.hidden ** -0.5, w.dtype)
+              for i in range(w.n_adapters)] for m in range(3)]
+    B_mod = [[_normal(seed ^ 0x3D, _ST_B, 16 * i + m, (r, widths[m]), r ** -0.5, w.dtype)
+              for i in range(w.n_adapters)] for m in range(3)]
+    v = copy.copy(w)
+    v.name = w.name + "+per-module"
+    v.A, v.B = [], []
+    for i in range(w.n_adapters):
+        v.A.append(np.ascontiguousarray(np.concatenate([A_mod[m][i] for m in range(3)], axis=1)))
+        Bf = np.zeros((w.rank, w.N), dtype=B_mod[0][i].dtype)     # zero bits are zero in both storage types
+        col = 0
+        for m in range(3):
+            Bf[m * r:(m + 1) * r, col:col + widths[m]] = B_mod[m][i]
+            col += widths[m]
+        v.B.append(Bf)
+    return v, A_mod, B_mod
+
+
 def sample_rows(w: Workload, n: int) -> np.ndarray:
     """Rows the oracle is timed/checked on: every segment's activation boundary +-2, first and last
     row of every segment, then evenly spaced rows up to n."""

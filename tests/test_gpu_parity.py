@@ -417,3 +417,34 @@ def test_a_later_layer_reuses_the_grouping_left_in_the_workspace(kw):
         assert np.array_equal(raw_bits(db.kc), raw_bits(fresh.kc)) and np.array_equal(raw_bits(db.vc), raw_bits(fresh.vc))
         ref = _oracle_full(wn)
         assert maxnorm_rel(to_f64(db.q), ref.q_out) <= TOL[wn.dtype]
+
+
+@pytest.mark.parametrize("dtype,rank,seq_lens", [("bf16", 48, (300, 41, 1, 77, 190)), ("bf16", 24, (33, 1, 7, 120)),
+                                                 ("f32", 15, (60, 9, 31))])
+def test_per_module_factors_as_block_structured_adapters(dtype, rank, seq_lens):
+    """Sec. 2.3 writes one low-rank update per module (Delta^Q, Delta^K, Delta^V).  Separate module factors of
+    rank r are handed to the library as A = [A^Q | A^K | A^V] of rank 3r with B^Q, B^K, B^V on B's block
+    diagonal; the result must match three separately projected modules (the oracle's per-module routine)."""
+    w0 = wl.small_mixed(dtype, seed=31, seq_lens=seq_lens, rank=rank)
+    w, A_mod, B_mod = wl.with_per_module_factors(w0)
+    print(f"[case] per-module factors {dtype} rank 3x{rank // 3} T={w.T}", flush=True)
+    db = DeviceBatch(w)
+    assert db.validate() == ab.ALORA_OK
+    db.forward()
+    x = wl.widen_f64(w.x, w.dtype)
+    Wf = wl.widen_f64(w.W, w.dtype)
+    W_mod = [Wf[:, : w.Nq], Wf[:, w.Nq: w.Nq + w.Nkv], Wf[:, w.Nq + w.Nkv:]]
+    A64 = [[wl.widen_f64(a, w.dtype) for a in A_mod[m]] for m in range(3)]
+    B64 = [[wl.widen_f64(b, w.dtype) for b in B_mod[m]] for m in range(3)]
+    _, act = oracle.classify(w.token_adapter_ids, w.token_seg_ids, w.token_positions, w.activation_start)
+    rows = np.arange(w.T, dtype=np.int32)
+    y = oracle.alora_rows_per_module(x, [np.ascontiguousarray(m) for m in W_mod], A64, B64, w.token_adapter_ids, act, rows)
+    tol = TOL[w.dtype]
+    assert maxnorm_rel(to_f64(db.q), y[:, : w.Nq]) <= tol
+    has = w.slot_mapping >= 0
+    sidx = torch.from_numpy(w.slot_mapping[has]).to("cuda")
+    assert maxnorm_rel(to_f64(db.kc[sidx]), y[has][:, w.Nq: w.Nq + w.Nkv]) <= tol
+    assert maxnorm_rel(to_f64(db.vc[sidx]), y[has][:, w.Nq + w.Nkv:]) <= tol
+    # the adapter term is there: adapted rows differ from the base projection
+    yb = oracle.base_rows(x, Wf, rows[act == 1][:8])
+    assert maxnorm_rel(y[act == 1][:8], yb) > 0.05

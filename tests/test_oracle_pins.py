@@ -374,7 +374,62 @@ def pin_variants_reduce_to_the_plain_form():
     assert np.array_equal(y, np.tile(bias, (T, 1)))
 
 
-PINS = [pin_variants_small_integers_exact, pin_variants_reduce_to_the_plain_form, pin_worked_example, pin_one_hot_closed_form, pin_activation_zero_is_lora,
+def _module_factors(rng, H, Nq, Nkv, r, L, ints=True):
+    """Separate (A^m_i, B^m_i) per module m in (Q, K, V) and the block-structured fused encoding of them:
+    A_i = [A^Q_i | A^K_i | A^V_i] of rank 3r, B_i with B^Q_i, B^K_i, B^V_i on its block diagonal."""
+    widths = (Nq, Nkv, Nkv)
+    draw = (lambda shape: _rand_ints(rng, shape)) if ints else (lambda shape: rng.standard_normal(shape))
+    A_mod = [[draw((H, r)) for _ in range(L)] for _ in range(3)]
+    B_mod = [[draw((r, widths[m])) for _ in range(L)] for m in range(3)]
+    A_fused, B_fused = [], []
+    N = Nq + 2 * Nkv
+    for i in range(L):
+        A_fused.append(np.concatenate([A_mod[m][i] for m in range(3)], axis=1))
+        Bf = np.zeros((3 * r, N))
+        col = 0
+        for m in range(3):
+            Bf[m * r:(m + 1) * r, col:col + widths[m]] = B_mod[m][i]
+            col += widths[m]
+        B_fused.append(Bf)
+    return A_mod, B_mod, A_fused, B_fused
+
+
+def pin_per_module_factors_exact():
+    """Sec. 2.3 writes one equation per module with its own Delta^Q, Delta^K, Delta^V.  On small integers
+    (every product and sum exact) the per-module routine must EQUAL the three equations written out with
+    Python integers, and the fused routine fed the block-structured encoding must EQUAL it too."""
+    rng = np.random.default_rng(91)
+    T, H, Nq, Nkv, r, L = 7, 4, 3, 2, 2, 2
+    x = _rand_ints(rng, (T, H))
+    W_mod = [_rand_ints(rng, (H, n)) for n in (Nq, Nkv, Nkv)]
+    A_mod, B_mod, A_f, B_f = _module_factors(rng, H, Nq, Nkv, r, L)
+    aid = np.array([0, 1, -1, 1, 0, 0, 1], np.int32)
+    act = np.array([1, 0, 0, 1, 0, 1, 1], np.uint8)
+    rows = np.arange(T, dtype=np.int32)
+    y = oracle.alora_rows_per_module(x, W_mod, A_mod, B_mod, aid, act, rows)
+    for t in range(T):
+        want = []
+        for m in range(3):
+            n_m = W_mod[m].shape[1]
+            for n in range(n_m):
+                v = sum(int(x[t, k]) * int(W_mod[m][k, n]) for k in range(H))
+                if act[t]:
+                    a = int(aid[t])
+                    for j in range(r):
+                        sj = sum(int(x[t, k]) * int(A_mod[m][a][k, j]) for k in range(H))
+                        v += sj * int(B_mod[m][a][j, n])
+                want.append(v)
+        assert [int(v) for v in y[t]] == want, t
+    fused = oracle.alora_rows(x, np.concatenate(W_mod, axis=1), A_f, B_f, aid, act, rows)
+    assert np.array_equal(fused, y)
+    # the modules really are separate: changing only the K module's factors changes only K columns
+    B_mod2 = [B_mod[0], [b + 1.0 for b in B_mod[1]], B_mod[2]]
+    y2 = oracle.alora_rows_per_module(x, W_mod, A_mod, B_mod2, aid, act, rows)
+    assert np.array_equal(y2[:, :Nq], y[:, :Nq]) and np.array_equal(y2[:, Nq + Nkv:], y[:, Nq + Nkv:])
+    assert not np.array_equal(y2[act == 1][:, Nq:Nq + Nkv], y[act == 1][:, Nq:Nq + Nkv])
+
+
+PINS = [pin_per_module_factors_exact, pin_variants_small_integers_exact, pin_variants_reduce_to_the_plain_form, pin_worked_example, pin_one_hot_closed_form, pin_activation_zero_is_lora,
         pin_pre_activation_rows_are_base_exactly, pin_zero_B_and_never_activated,
         pin_blend_equals_select, pin_mask_closed_form_counts, pin_group_matches_stable_sort,
         pin_brute_force_exact, pin_linearity, pin_row_permutation, pin_paged_store,
