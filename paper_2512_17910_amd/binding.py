@@ -11,8 +11,7 @@ import os
 from typing import List, Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# ALORA_QKV_LIB selects another build of the same C ABI (used to time kernel variants)
-LIB_PATH = os.environ.get("ALORA_QKV_LIB") or os.path.join(HERE, "libalora_qkv.so")
+LIB_PATH = os.path.join(HERE, "libalora_qkv.so")
 
 ALORA_F32, ALORA_BF16 = 0, 1
 ALORA_OK, ALORA_EINVAL, ALORA_ESHAPE, ALORA_EWORKSPACE, ALORA_EHIP, ALORA_EDATA, ALORA_ENOMEM = 0, -1, -2, -3, -4, -5, -6

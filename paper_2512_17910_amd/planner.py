@@ -21,11 +21,19 @@ class PlanBatch(ctypes.Structure):
 
 
 _declared = False
+_planner_lib = None   # a separately built planner (the host-only translation unit under CPU sanitizers); None: the library
+
+
+def use_planner_library(handle) -> None:
+    """Point this binding at another build of the planner's C ABI (ctypes handle), or back at the library (None)."""
+    global _planner_lib, _declared
+    _planner_lib = handle
+    _declared = False
 
 
 def _L():
     global _declared
-    L = lib()
+    L = _planner_lib if _planner_lib is not None else lib()
     if not _declared:
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.alora_planner_create.argtypes = [i32, i64, ctypes.POINTER(vp)]
