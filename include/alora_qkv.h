@@ -256,8 +256,8 @@ int alora_qkv_validate(const int32_t *token_adapter_ids, const int32_t *activati
                        const int64_t *slot_mapping, int32_t block_size, const alora_dims *dims);
 
 /*
- * Tuning override for tests and benchmarks of the bf16 path (process-wide, not thread-safe; set it
- * before querying the workspace size).  By default the library picks, from (T, hidden, N) alone,
+ * Tuning override for tests and benchmarks of the bf16 path (process-wide: one atomic word, so a call on
+ * another thread sees the old or the new setting, never a mix; set it before querying the workspace size).  By default the library picks, from (T, hidden, N) alone,
  * the width of the projection kernel's feature tile and, for batches too small to fill the chip,
  * into how many splits of the hidden dimension the base product is cut (the small-batch path:
  * split projection + a finishing kernel over the grouped rows).

@@ -20,6 +20,7 @@ struct Profile {
     std::vector<hipEvent_t> ev0, ev1;
 };
 static Profile g_prof;
+static std::mutex g_prof_mutex;   // forward calls of several host threads may meet the benchmark aid
 
 static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -276,8 +277,15 @@ static int forward_on(const void *x, const int32_t *token_adapter_ids, const int
     f.x = x; f.W = W_qkv; f.aid = token_adapter_ids; f.start = activation_start; f.slot = slot_mapping;
     f.q = q_out; f.kc = k_cache; f.vc = v_cache;
 
-    bool timed = allow_timing && g_prof.on && g_prof.used < (int)g_prof.ev0.size();
-    if (timed) timed = (g_prof.seen++ % g_prof.every) == 0;
+    // (the lock is held over the launches only while the benchmark aid is switched on)
+    std::unique_lock<std::mutex> prof_lock(g_prof_mutex, std::defer_lock);
+    bool timed = false;
+    if (allow_timing) {
+        prof_lock.lock();
+        timed = g_prof.on && g_prof.used < (int)g_prof.ev0.size();
+        if (timed) timed = (g_prof.seen++ % g_prof.every) == 0;
+        if (!timed) prof_lock.unlock();
+    }
     // decode-sized bf16 batches: grouping and shrink ride in the projection kernel (two launches in all)
     const bool prep_inside = prep_in_projection(f);
     int e = (prep_inside || reuse_grouping) ? 0 : launch_classify_group(f);
@@ -410,6 +418,7 @@ int alora_qkv_profile_begin(int max_calls) { return alora_qkv_profile_begin_ever
 int alora_qkv_profile_begin_every(int max_calls, int every)
 {
     if (max_calls <= 0 || max_calls > (1 << 20) || every < 1) return ALORA_EINVAL;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (g_prof.on) return ALORA_EINVAL;
     const int pairs = (max_calls + every - 1) / every;   // calls that can be measured
     try {
@@ -432,6 +441,7 @@ int alora_qkv_profile_begin_every(int max_calls, int every)
 
 int alora_qkv_profile_end(double *avg_ms, int *n_calls)
 {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (!g_prof.on) return ALORA_EINVAL;
     g_prof.on = false;
     double sum = 0.0;

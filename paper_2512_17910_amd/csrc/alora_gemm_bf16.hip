@@ -34,6 +34,7 @@
 //     row per 32x32 block and four consecutive features per register quad, so the select is a
 //     per-lane condition and stores are 8-byte vectors.
 #include <algorithm>
+#include <atomic>
 #include "alora_internal.h"
 #include "alora_group_small.h"
 #include "alora_shrink_rows.h"
@@ -631,16 +632,16 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 // Everything below depends on (T, hidden, N) and on the tuning overrides only, never on adapter
 // data: a call in which every adapter id is -1 is tiled exactly like the adapted call, which is
 // what makes rows that keep the base output bit-identical between the two.
-static int g_force_ntw = 0, g_force_splits = 0;
+// Process-wide override, one word (feature tiles in the low byte, splits above it) so that a reader never
+// sees half of a new setting.
+static std::atomic<int> g_force_tuning{0};
 
-void set_gemm_tuning(int ntw, int splits)
-{
-    g_force_ntw = ntw;
-    g_force_splits = splits;
-}
+void set_gemm_tuning(int ntw, int splits) { g_force_tuning.store((ntw & 0xff) | (splits << 8), std::memory_order_relaxed); }
 
 GemmPlan plan_gemm(int T, int H, int N)
 {
+    const int forced = g_force_tuning.load(std::memory_order_relaxed);
+    const int g_force_ntw = forced & 0xff, g_force_splits = forced >> 8;
     constexpr int CUS = 256;                       // MI355X
     const int cand[3] = {4, 3, 2};
     const double unit[3] = {1.0, 0.78, 0.56};      // time of one K-slice relative to the 256-wide tile

@@ -150,3 +150,35 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_model_of_the_ranged_shrink_combine():
+    """Host-side model of what the ranged shrink does with a block's partial results: every range of the
+    hidden dimension accumulates in fp32, the partials are added in RANGE ORDER whichever range finishes last,
+    and the sum is handed on as hi = bf16(S), lo = bf16(S - hi).  On small integers every fp32 sum is exact,
+    so the model must equal the exact x . A for any number of ranges and any arrival order, and hi + lo must
+    give S back exactly while S needs at most 16 significant bits."""
+    import numpy as np
+    from paper_2512_17910_amd import workloads as wl
+    rng = np.random.default_rng(5)
+    H, r, rows = 512, 8, 32
+    x = rng.integers(-3, 4, (rows, H)).astype(np.float32)
+    A = rng.integers(-3, 4, (H, r)).astype(np.float32)
+    exact = x.astype(np.int64) @ A.astype(np.int64)
+    for n_ranges in (1, 2, 4, 8):
+        kper = H // n_ranges
+        parts = []
+        for g in range(n_ranges):
+            acc = np.zeros((rows, r), np.float32)
+            for k in range(g * kper, (g + 1) * kper):          # fp32 accumulation, k ascending
+                acc = acc + x[:, k:k + 1] * A[k:k + 1, :]
+            parts.append(acc)
+        for arrival in (list(range(n_ranges)), list(reversed(range(n_ranges)))):
+            # whoever arrives last adds the partials in range order, not in arrival order
+            S = np.zeros((rows, r), np.float32)
+            for g in range(n_ranges):
+                S = S + parts[g]
+            assert arrival[-1] in range(n_ranges) and np.array_equal(S.astype(np.int64), exact)
+        hi = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(S))
+        lo = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(S - hi))
+        assert np.array_equal(hi + lo, S)
