@@ -87,16 +87,42 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
     return r;
 }
 
-// 64 lanes x 16 bytes from the buffer straight into LDS at lds_addr + 16*lane.  Written as an
-// assembly statement: the kernel orders these copies against its LDS reads itself (wait counts and
-// barriers in the main loop), which the compiler's own bookkeeping of such loads would override
-// with waits for all of them.
-__device__ __forceinline__ void load_lds16(rsrc_t rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset)
+// 64 lanes x 16 bytes from the buffer straight into LDS at M0 + IMM + 16*lane.  Written as assembly
+// statements: the kernel orders these copies against its LDS reads itself (wait counts and barriers
+// in the main loop), which the compiler's own bookkeeping of such loads would override with waits
+// for all of them.
+// The LDS address is not set per copy: the copies of one operand tile share one M0 and differ in the
+// instruction's immediate offset (two scalar instructions per slice and wavefront instead of two per
+// copy).  That offset also advances the global address, which the per-copy vector offsets take back
+// (lds_copy_voffset); to keep those non-negative for every shape, descriptors made by make_rsrc_copy
+// start LDS_COPY_BIAS bytes early (no lane ever addresses the bytes before the buffer: every valid
+// offset plus its immediate is at least LDS_COPY_BIAS).
+constexpr uint32_t LDS_COPY_BIAS = 4096;
+constexpr uint32_t LDS_COPY_STEP = 1024;   // LDS bytes between consecutive copies of one operand tile
+__device__ __forceinline__ rsrc_t make_rsrc_copy(const void *base, uint32_t bytes)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
-                 : "memory");
+    return make_rsrc((const char *)base - LDS_COPY_BIAS, bytes + LDS_COPY_BIAS);
+}
+// vector offset of copy j (0..3) of a tile whose element sits `bytes` into the descriptor's buffer
+__device__ __forceinline__ uint32_t lds_copy_voffset(uint32_t bytes, int j) { return bytes + LDS_COPY_BIAS - LDS_COPY_STEP * j; }
+__device__ __forceinline__ void set_lds_base(uint32_t lds_addr)
+{
+    // (one wait state between a write of M0 and an LDS-direct load)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds_addr) : "memory");
+}
+template <int IMM>
+__device__ __forceinline__ void load_lds16_imm(rsrc_t rsrc, uint32_t voffset, uint32_t soffset)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, %2 offen offset:%3 lds" : : "v"(voffset), "s"(rsrc), "s"(soffset), "n"(IMM) : "memory");
+}
+__device__ __forceinline__ void load_lds16(int j, rsrc_t rsrc, uint32_t voffset, uint32_t soffset)
+{
+    switch (j) {
+    case 0: load_lds16_imm<0>(rsrc, voffset, soffset); break;
+    case 1: load_lds16_imm<LDS_COPY_STEP>(rsrc, voffset, soffset); break;
+    case 2: load_lds16_imm<2 * LDS_COPY_STEP>(rsrc, voffset, soffset); break;
+    default: load_lds16_imm<3 * LDS_COPY_STEP>(rsrc, voffset, soffset); break;
+    }
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const lds_byte *p) { return (uint32_t)(uintptr_t)p; }
 
@@ -249,14 +275,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
     // ---- the slice sequence -------------------------------------------------------------------
-    const rsrc_t rx = make_rsrc(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
-    const rsrc_t rw = make_rsrc(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
-    const rsrc_t rs = make_rsrc(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
+    const rsrc_t rx = make_rsrc_copy(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
+    const rsrc_t rw = make_rsrc_copy(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
+    const rsrc_t rs = make_rsrc_copy(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
     uint32_t vxb[4], vwb[NCW];
 #pragma unroll
-    for (int ii = 0; ii < 4; ++ii) vxb[ii] = (uint32_t)(x_row(ii, lane) * g.H + 8 * x_chunk(ii, lane)) * 2;
+    for (int ii = 0; ii < 4; ++ii) vxb[ii] = lds_copy_voffset((uint32_t)(x_row(ii, lane) * g.H + 8 * x_chunk(ii, lane)) * 2, ii);
 #pragma unroll
-    for (int jj = 0; jj < NCW; ++jj) vwb[jj] = w_col_ok(jj, lane) ? (uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
+    for (int jj = 0; jj < NCW; ++jj)
+        vwb[jj] = w_col_ok(jj, lane) ? lds_copy_voffset((uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2, jj) : OOR;
     const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
     // base K-slices of this workgroup: all of them, or the range of its split
     const int kt0 = SPLIT ? by * g.kps : 0;
@@ -267,8 +294,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // (c = 4..) instructions
     auto copy = [&](int c, rsrc_t r_x, const uint32_t (&vx)[4], uint32_t sx, rsrc_t r_w, const uint32_t (&vw)[NCW],
                     uint32_t sw, uint32_t sta) {
-        if (c < 4) load_lds16(r_x, sta + (uint32_t)(64 * w + 16 * c) * (BK * 2), vx[c], sx);
-        else load_lds16(r_w, sta + W_OFF + (uint32_t)(8 * w + RPW * (c - 4)) * WPITCH, vw[c - 4], sw);
+        static_assert(16 * BK * 2 == LDS_COPY_STEP && RPW * WPITCH == LDS_COPY_STEP && NCW <= 4, "immediate offsets of the copies");
+        if (c == 0) set_lds_base(sta + (uint32_t)(64 * w) * (BK * 2));
+        if (c == 4) set_lds_base(sta + W_OFF + (uint32_t)(8 * w) * WPITCH);
+        if (c < 4) load_lds16(c, r_x, vx[c], sx);
+        else load_lds16(c - 4, r_w, vw[c - 4], sw);
     };
     // Base slice s of this workgroup.  Slices past the end repeat the last one: every step issues
     // the same number of copies, which is what the in-order wait counts assume.
@@ -341,20 +371,20 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             const int a = __builtin_amdgcn_readfirstlane(plist[j]);
             const int ra = __builtin_amdgcn_readfirstlane((int)g.ranks.r[a]);   // rows of B_a; S columns past it are zero, B rows past it do not exist
             const rsrc_t rb =
-                make_rsrc((const bf16_t *)B.p[a] + n0, (uint32_t)(ra * g.N - n0) * 2);
+                make_rsrc_copy((const bf16_t *)B.p[a] + n0, (uint32_t)(ra * g.N - n0) * 2);
             uint32_t vx[4], vw[NCW];
 #pragma unroll
             for (int ii = 0; ii < 4; ++ii) {
                 const int row = x_row(ii, lane), kk = k0 + 8 * x_chunk(ii, lane);
                 const bool ok = (arow[row] == a) & (kk < g.kx);
-                vx[ii] = ok ? (uint32_t)(row * g.kx + kk) * 2 : OOR;
+                vx[ii] = ok ? lds_copy_voffset((uint32_t)(row * g.kx + kk) * 2, ii) : OOR;
             }
 #pragma unroll
             for (int jj = 0; jj < NCW; ++jj) {
                 const int kk = k0 + w_k(jj, lane);
                 const int srow = kk >= g.r ? kk - g.r : kk;   // [B ; B]: the hi and the lo half meet the same rows
                 const bool ok = (kk < g.kx) & (srow < ra) & w_col_ok(jj, lane);
-                vw[jj] = ok ? (uint32_t)(srow * g.N + 8 * w_chunk(jj, lane)) * 2 : OOR;
+                vw[jj] = ok ? lds_copy_voffset((uint32_t)(srow * g.N + 8 * w_chunk(jj, lane)) * 2, jj) : OOR;
             }
 #pragma unroll
             for (int c = 0; c < NC; ++c) copy(c, rs, vx, 0, rb, vw, 0, sa[NST - 1]);
@@ -402,7 +432,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         constexpr int NM = 4 * NTW, CI = NTW == 2 ? 2 : 3;
 #pragma unroll
         for (int gm = 0; gm < 2 * NM; ++gm) {
-            const int half = gm / NM, m = gm % NM, a = m / 4, b = m % 4;
+            // token tiles in snake order (0..3, 3..0, ...): across a change of the weight fragment the token
+            // fragment stays, so one of the two operands repeats from every MFMA to the next.  The kernel
+            // runs at the clock the power limit allows, and less switching on the operand paths is clock:
+            // measured 1 to 3 % on the main loop; each accumulator still sees its slices in the same order.
+            const int half = gm / NM, m = gm % NM, a = m / 4, b = (a & 1) ? 3 - m % 4 : m % 4;
             if (half == 0) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[a], xf0[b], acc[a][b], 0, 0, 0);
             else acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[a], xf1[b], acc[a][b], 0, 0, 0);
             // unit u of the other fragment buffer, in the order the MFMAs will want them: the first
