@@ -56,17 +56,30 @@ class AloraError(RuntimeError):
 _lib = None
 
 
+_lib_path = LIB_PATH
+
+
+def use_probe_library(path: str) -> None:
+    """Make this process load a probe build of the library (see probe.py) instead of the product build.  Only
+    before the first call into the library, and only the probe script does it: a probe build computes wrong
+    results on purpose."""
+    global _lib_path
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _lib_path = path
+
+
 def lib() -> ctypes.CDLL:
     """The loaded C-ABI library; raises if it has not been built."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_17910_amd.build` "
+        if not os.path.exists(_lib_path):
+            raise ImportError(f"{_lib_path} is missing: build it with `python -m paper_2512_17910_amd.build` "
                               "(there is no non-HIP fallback)")
         # torch first: its HIP runtime must be the one this process uses (a library loaded before it would
         # bring the system's copy of the runtime in beside torch's, and the two do not share devices)
         import torch  # noqa: F401
-        L = ctypes.CDLL(LIB_PATH)
+        L = ctypes.CDLL(_lib_path)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         L.alora_qkv_workspace_bytes.argtypes = [ctypes.POINTER(AloraDims), ctypes.POINTER(sz)]
         L.alora_qkv_workspace_layout.argtypes = [ctypes.POINTER(AloraDims), ctypes.POINTER(AloraWsLayout)]

@@ -139,9 +139,31 @@ __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p, int pitch)
 // SPLIT: small-batch mode.  The workgroup index selects a tile and a range of K-slices; the kernel only accumulates the
 // base product over that range and stores the fp32 accumulators to g.partial[split][T][N]; adapters,
 // rounding and the q_out / cache stores are left to the finishing kernel.
+// Probe builds (-DALORA_PROBE=bits, a library of their own that only the package's probe script loads; the
+// product library is built without and contains none of this).  Bit 1: the main loop issues no global -> LDS
+// copies; bit 2: it reads no fragments from LDS (both leave the MFMA sequence as it is and the results wrong);
+// bit 4: every workgroup records when it passed the kernel's phases (100 MHz counter) and every wavefront the
+// shader-clock cycles of its main loop, into the buffer alora_probe_set_buffer names; bit 8: every workgroup
+// fetches the operands of tile (0, 0), so that the copies hit in L2.
+#ifndef ALORA_PROBE
+#define ALORA_PROBE 0
+#endif
+#if ALORA_PROBE
+constexpr int PROBE_MAX_WGS = 4096;
+__device__ unsigned long long *g_probe;   // [PROBE_MAX_WGS][8] phase stamps, then [PROBE_MAX_WGS][4] loop cycles per wavefront
+#define PROBE_STAMP(i)                                                                                   \
+    do {                                                                                                 \
+        if (g_probe && threadIdx.x == 0 && blockIdx.x < PROBE_MAX_WGS)                                   \
+            g_probe[(size_t)blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memrealtime();                     \
+    } while (0)
+#else
+#define PROBE_STAMP(i)
+#endif
+
 template <int NTW, bool SPLIT, bool ROPE = false>
 __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmArgs g, PtrTable B, PtrTable A)
 {
+    PROBE_STAMP(0);   // entry
     constexpr int BN = 64 * NTW;
     // Ring geometry.  128-feature tiles keep weight rows of 256 bytes, which makes a stage 24 KB and
     // leaves room for six stages instead of four: four slices in flight instead of two, which is
@@ -275,8 +297,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
     // ---- the slice sequence -------------------------------------------------------------------
+#if ALORA_PROBE & 8
+    // every workgroup fetches the operands of tile (0, 0): the same instruction stream with (almost) no L2 misses
+    const rsrc_t rx = make_rsrc_copy(g.x, (uint32_t)min(g.T, BM) * g.H * 2);
+    const rsrc_t rw = make_rsrc_copy(g.W, (uint32_t)(g.H * g.N) * 2);
+#else
     const rsrc_t rx = make_rsrc_copy(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
     const rsrc_t rw = make_rsrc_copy(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
+#endif
     const rsrc_t rs = make_rsrc_copy(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
     uint32_t vxb[4], vwb[NCW];
 #pragma unroll
@@ -362,6 +390,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         n_exp = __builtin_amdgcn_readfirstlane(n_present) * epa;
     }
 
+    PROBE_STAMP(1);   // ring prologue issued, the tile's rows known
     // ---- 2. expand first, then select ------------------------------------------------------
     // One slice at a time through the last stage (few slices, not pipelined): 32 k of
     // [S_hi | S_lo] for the rows of adapter a (zeros elsewhere) against the matching rows of [B_a ; B_a].
@@ -422,6 +451,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // Within a step the source order is the issue order: behind every MFMA one fragment read for
     // the next 16 k until they are all issued, and one copy behind every third MFMA, which keeps the
     // demand on the vector memory pipe (64 B/clk per CU) uniform.
+#if ALORA_PROBE
+    const unsigned long long probe_loop_begin = __builtin_readcyclecounter();
+#endif
     auto step = [&](int s, const lds_byte *cur, const lds_byte *nxt, uint32_t tgt) {
         // this wavefront's copies of slices <= s+1 have landed (those of slices s+2 .. s+NST-2 may be
         // in flight); behind the barrier that holds for every wavefront, and all of them are done
@@ -442,7 +474,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             // unit u of the other fragment buffer, in the order the MFMAs will want them: the first
             // five behind MFMAs 0..4, the rest behind every second MFMA after that
             const int u = m < 5 ? m : ((m - 5) % 2 == 0 ? 5 + (m - 5) / 2 : -1);
-            if (u >= 0 && u < 4 + NTW) {
+            if (u >= 0 && u < 4 + NTW && !(ALORA_PROBE & 2)) {
                 if (half == 0) {
                     if (u == 0) wf1[0] = read_w(cur, 1, 0);
                     else if (u <= 4) xf1[u - 1] = read_x(cur, 1, u - 1);
@@ -453,7 +485,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                     else wf0[u - 4] = read_w(nxt, 0, u - 4);
                 }
             }
-            if (gm % CI == 1 && gm / CI < NC) copy(gm / CI, rx, vxb, sx, rw, vwb, sw, tgt);
+            if (gm % CI == 1 && gm / CI < NC && !(ALORA_PROBE & 1)) copy(gm / CI, rx, vxb, sx, rw, vwb, sw, tgt);
         }
         // the same order, spelled out for the instruction scheduler (MFMA, then the LDS reads of its unit)
 #pragma unroll
@@ -467,7 +499,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             }
         }
     };
+    PROBE_STAMP(2);   // expand and select done
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NC * (NST - 2)) : "memory");
+    PROBE_STAMP(3);   // first slices landed
     load_frags(st0, 0, wf0, xf0);
     for (int s = 0; s < n_base; s += NST) {
 #pragma unroll
@@ -475,6 +509,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             if (u == 0 || s + u < n_base) step(s + u, st[u], st[(u + 1) % NST], sa[(u + NST - 1) % NST]);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    PROBE_STAMP(4);   // main loop done
+#if ALORA_PROBE
+    if (g_probe && lane == 0 && blockIdx.x < PROBE_MAX_WGS)
+        g_probe[(size_t)PROBE_MAX_WGS * 8 + (size_t)blockIdx.x * 4 + w] = __builtin_readcyclecounter() - probe_loop_begin;
+#endif
 
     // ---- 4. round and store ------------------------------------------------------------------
     // D[i][j]: i = feature (8g + 4*lh + jj, register 4g + jj), j = token (li).  Each wavefront turns
@@ -660,7 +699,23 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             }
         }
     }
+#if ALORA_PROBE
+    PROBE_STAMP(5);   // stores issued
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    PROBE_STAMP(6);   // stores left the wavefront
+#endif
 }
+
+#if ALORA_PROBE
+// Device buffer of at least alora_probe_buffer_bytes() bytes (zeroed by the caller) that the probe build's
+// kernels write; null switches the recording off.  Exists in probe builds only.
+extern "C" __attribute__((visibility("default"))) size_t alora_probe_buffer_bytes(void) { return (size_t)PROBE_MAX_WGS * (8 + 4) * 8; }
+extern "C" __attribute__((visibility("default"))) int alora_probe_set_buffer(void *device_buffer)
+{
+    unsigned long long *p = (unsigned long long *)device_buffer;
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_probe), &p, sizeof(p));
+}
+#endif
 
 // ---- host side: how a call of given sizes is tiled ---------------------------------------------
 // Everything below depends on (T, hidden, N) and on the tuning overrides only, never on adapter
