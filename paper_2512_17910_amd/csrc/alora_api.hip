@@ -43,8 +43,9 @@ static int check_dims(const alora_dims *d)
     if (d->dtype == ALORA_BF16) {
         if (d->hidden % 64 || Nq % 8 || Nkv % 8) return ALORA_ESHAPE;
         if (d->n_adapters > 0 && d->rank % 8) return ALORA_ESHAPE;
-        // 32-bit byte offsets inside the weight matrix (buffer addressing)
-        if ((long long)d->hidden * (Nq + 2 * Nkv) * 2 >= (1ll << 31)) return ALORA_ESHAPE;
+        // 32-bit byte offsets inside the weight matrix (buffer addressing; the projection's descriptors start
+        // 4 KiB before the matrix and offsets from 2^31 on mark masked lanes)
+        if ((long long)d->hidden * (Nq + 2 * Nkv) * 2 + 4096 >= (1ll << 31)) return ALORA_ESHAPE;
         // 32-bit byte offsets of the gathered token rows in the shrink
         if (d->n_adapters > 0 && (long long)d->T * d->hidden * 2 > 0xfffffff0ll) return ALORA_ESHAPE;
     } else {

@@ -84,7 +84,7 @@ def run_one(bits: int, config: int, calls: int, rows: int = 0) -> None:
     n_wg = nbytes // 8 // 12
     st = raw[: n_wg * 8].reshape(n_wg, 8)
     cyc = raw[n_wg * 8:].reshape(n_wg, 4)
-    live = st[:, 0] > 0
+    live = (st[:, 0] > 0) & (st[:, 6] > 0)      # workgroups that ran the projection (not the grouping/shrink ones of a decode batch)
     st, cyc = st[live], cyc[live]
     us = (st[:, :7] - st[:, :1]) * 0.01          # the counter runs at 100 MHz
     d = np.diff(us, axis=1)
@@ -140,7 +140,7 @@ def gaps(config: int) -> None:
 def main() -> None:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("what", choices=["build", "run", "run-one", "gaps"])
-    ap.add_argument("--config", type=int, default=2, choices=[2, 4, 5, 6])
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5, 6])
     ap.add_argument("--calls", type=int, default=30)
     ap.add_argument("--bits", type=int, default=4, choices=sorted(VARIANTS))
     ap.add_argument("--rows", type=int, default=0, help="run: a batch of this many rows in configuration 2's shapes instead")
