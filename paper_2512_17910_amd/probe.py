@@ -4,6 +4,7 @@
     python -m paper_2512_17910_amd.probe run --config 2   # on the GPU: one line per build
     python -m paper_2512_17910_amd.probe run --rows 1024  # the same with 128 of the 256 compute units busy
     python -m paper_2512_17910_amd.probe gaps --config 2  # on the GPU, product build: idle time between calls
+    python -m paper_2512_17910_amd.probe mfma             # on the GPU: MFMAs alone, random operands in registers
 
 A probe build (-DALORA_PROBE=bits, csrc/alora_gemm_bf16.hip) is the product kernel with time stamps, and
 optionally with the main loop's global -> LDS copies (bit 1) and/or its LDS fragment reads (bit 2) left out, or
@@ -43,6 +44,10 @@ def build() -> None:
         cmd = ["hipcc", *b.FLAGS, f"-DALORA_PROBE={bits}", "-o", probe_path(bits), *srcs]
         subprocess.run(cmd, check=True)
         print("built", probe_path(bits))
+    exe = os.path.join(PROBE_DIR, "mfma_rate")
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                    "-Wno-unused-command-line-argument", "-o", exe, os.path.join(HERE, "probe_src", "mfma_rate.hip")], check=True)
+    print("built", exe)
 
 
 def _batch(config: int, rows: int = 0):
@@ -139,7 +144,7 @@ def gaps(config: int) -> None:
 
 def main() -> None:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["build", "run", "run-one", "gaps"])
+    ap.add_argument("what", choices=["build", "run", "run-one", "gaps", "mfma"])
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5, 6])
     ap.add_argument("--calls", type=int, default=30)
     ap.add_argument("--bits", type=int, default=4, choices=sorted(VARIANTS))
@@ -151,6 +156,8 @@ def main() -> None:
         run(a.config, a.calls, a.rows)
     elif a.what == "run-one":
         run_one(a.bits, a.config, a.calls, a.rows)
+    elif a.what == "mfma":
+        raise SystemExit(subprocess.run([os.path.join(PROBE_DIR, "mfma_rate")]).returncode)
     else:
         gaps(a.config)
 
