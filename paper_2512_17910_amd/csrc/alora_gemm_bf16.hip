@@ -220,12 +220,13 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                 int *scr = (int *)stage5;
                 int grp, cnt;
                 const int *rows = group_small(g.prep, g.T, g.L, e, range == 0, scr, grp, cnt);
-                if (grp < 0 || grp >= g.L) return;   // unused entry or the rows that keep the base output
+                if (grp < 0 || grp >= g.L) { PROBE_STAMP(7); return; }   // unused entry or the rows that keep the base output
                 const int kbeg = range * g.prep_kper;
                 shrink_rows<256, 1, false>(g.x, (const bf16_t *)A.p[grp], g.ranks.r[grp], rows, g.H, g.r,
                                            (uint32_t)((size_t)g.T * g.H * 2), g.T, kbeg, min(g.H, kbeg + g.prep_kper), range,
                                            g.prep_ranges, nullptr, g.S_out, stage0, stage1, stage2, stage3,
                                            (float (*)[1][32][33])stage4, scr + GROUP_SMALL_SCRATCH);
+                PROBE_STAMP(7);   // grouping and shrink of this entry done
             }
             return;
         }
