@@ -144,7 +144,8 @@ __device__ __forceinline__ bf16x8 read_w_frag(const lds_byte *p, int pitch)
 // copies; bit 2: it reads no fragments from LDS (both leave the MFMA sequence as it is and the results wrong);
 // bit 4: every workgroup records when it passed the kernel's phases (100 MHz counter) and every wavefront the
 // shader-clock cycles of its main loop, into the buffer alora_probe_set_buffer names; bit 8: every workgroup
-// fetches the operands of tile (0, 0), so that the copies hit in L2.
+// fetches the operands of tile (0, 0), so that the copies hit in L2; bit 16: the weight tile is addressed as if W were
+// stored tile by tile, a contiguous stream per workgroup.
 #ifndef ALORA_PROBE
 #define ALORA_PROBE 0
 #endif
@@ -302,18 +303,24 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // every workgroup fetches the operands of tile (0, 0): the same instruction stream with (almost) no L2 misses
     const rsrc_t rx = make_rsrc_copy(g.x, (uint32_t)min(g.T, BM) * g.H * 2);
     const rsrc_t rw = make_rsrc_copy(g.W, (uint32_t)(g.H * g.N) * 2);
+#elif ALORA_PROBE & 16
+    // the weight tile addressed as if W were stored tile by tile ([N / BN][hidden][BN]): a workgroup's weight
+    // stream is then one contiguous range (timing of that layout; W is not stored that way, results are wrong)
+    const rsrc_t rx = make_rsrc_copy(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
+    const rsrc_t rw = make_rsrc_copy(g.W + (size_t)nt * g.H * BN, (uint32_t)(g.H * BN) * 2);
 #else
     const rsrc_t rx = make_rsrc_copy(g.x + (size_t)m0 * g.H, (uint32_t)rows_valid * g.H * 2);
     const rsrc_t rw = make_rsrc_copy(g.W + n0, (uint32_t)(g.H * g.N - n0) * 2);
 #endif
+    const int w_pitch = (ALORA_PROBE & 16) ? BN : g.N;   // elements between consecutive k rows of the weight tile
     const rsrc_t rs = make_rsrc_copy(g.S_hl + (size_t)m0 * g.kx, (uint32_t)rows_valid * g.kx * 2);
     uint32_t vxb[4], vwb[NCW];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii) vxb[ii] = lds_copy_voffset((uint32_t)(x_row(ii, lane) * g.H + 8 * x_chunk(ii, lane)) * 2, ii);
 #pragma unroll
     for (int jj = 0; jj < NCW; ++jj)
-        vwb[jj] = w_col_ok(jj, lane) ? lds_copy_voffset((uint32_t)(w_k(jj, lane) * g.N + 8 * w_chunk(jj, lane)) * 2, jj) : OOR;
-    const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * g.N * 2;
+        vwb[jj] = w_col_ok(jj, lane) ? lds_copy_voffset((uint32_t)(w_k(jj, lane) * w_pitch + 8 * w_chunk(jj, lane)) * 2, jj) : OOR;
+    const uint32_t xstep = BK * 2, wstep = (uint32_t)BK * w_pitch * 2;
     // base K-slices of this workgroup: all of them, or the range of its split
     const int kt0 = SPLIT ? by * g.kps : 0;
     const int KT = SPLIT ? min(g.H / BK, kt0 + g.kps) : g.H / BK;

@@ -27,7 +27,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 PROBE_DIR = os.path.join(HERE, "probe_builds")
 VARIANTS = {4: "product instruction stream", 5: "no global->LDS copies in the main loop",
             6: "no LDS fragment reads in the main loop", 7: "neither: the MFMA sequence alone",
-            12: "every workgroup fetches tile (0,0)'s operands: copies without L2 misses"}
+            12: "every workgroup fetches tile (0,0)'s operands: copies without L2 misses",
+            20: "weights addressed as if stored tile by tile: one contiguous stream per workgroup"}
 PHASES = ["entry", "ring issued, rows known", "expand + select done", "first slices landed", "main loop done",
           "stores issued", "stores drained"]
 
