@@ -95,6 +95,10 @@ def test_every_tiling_matches_the_oracle(tuning, ft, sp):
     _check_full(wl.small_mixed("bf16", seed=11, rank=8, n_adapters=2, hidden=64, seq_lens=(70, 200, 9)))
     _check_full(wl.small_mixed("bf16", seed=12, rank=32, n_adapters=4, hidden=448, n_q_heads=3, head_dim=64,
                                seq_lens=(260, 31)))
+    # the narrowest matrices the bf16 path takes: 24 output features (a weight row is shorter than the step
+    # between two copies of a tile), rank 8 (so is a row of the shrink result)
+    _check_full(wl.small_mixed("bf16", seed=13, rank=8, n_adapters=3, hidden=64, n_q_heads=1, n_kv_heads=1, head_dim=8,
+                               seq_lens=(40, 7, 300)))
 
 
 @pytest.mark.parametrize("ft,sp", [(4, 1), (2, 4)], ids=["fused", "split"])
