@@ -176,23 +176,39 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     constexpr int RPW = 64 / LPW;                      // weight rows per copy instruction
     constexpr int NCW = BK / RPW / 4;                  // weight-tile copy instructions per wavefront and slice
     constexpr int NC = 4 + NCW;                        // copy instructions per wavefront and slice
-    __shared__ __attribute__((aligned(16))) unsigned char stage0[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char stage1[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char stage2[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char stage3[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char stage4[NST > 4 ? STAGE_BYTES : 16];
-    __shared__ __attribute__((aligned(16))) unsigned char stage5[NST > 4 ? STAGE_BYTES : 16];
-    __shared__ int arow[BM];                       // effective adapter per tile row
-    __shared__ int present[ALORA_MAX_ADAPTERS];
-    __shared__ int plist[ALORA_MAX_ADAPTERS];      // adapters present in this tile, ascending
-    __shared__ int n_present;
-    __shared__ int64_t slot_lds[BM];               // cache slot per tile row (-1: no K/V write)
-    lds_byte *const st0 = (lds_byte *)stage0;
-    lds_byte *const st1 = (lds_byte *)stage1;
-    lds_byte *const st2 = (lds_byte *)stage2;
-    lds_byte *const st3 = (lds_byte *)stage3;
-    lds_byte *const st[6] = {st0, st1, st2, st3, (lds_byte *)stage4, (lds_byte *)stage5};
-    lds_byte *const st_x = st[NST - 1];   // the stage the expand phase works in
+    // PAIRED (the 192- and 256-wide tiles): token slices and weight slices live in rings of their own, six token
+    // areas and four weight areas of 16 KB, and the token copies of a step cover HALF the tile's rows for TWO
+    // consecutive slices -- the two 64-byte halves of every 128-byte line of x are requested by neighbouring
+    // instructions, and the second one finds the line on its way.  Measured on the main loop: 4 % (the kernel runs
+    // at the clock its power draw allows, and a line fetched once from L2 instead of twice is clock).  A token
+    // area then lives one step longer than a weight area, hence the separate rings; all 160 KB are ring, and the
+    // small arrays below sit in a token area that the main loop does not reach before they are done with.
+    constexpr bool PAIRED = NTW != 2;
+    constexpr int NXA = PAIRED ? 6 : NST, NWA = PAIRED ? 4 : NST;          // token areas, weight areas
+    constexpr uint32_t X_AREA = 16384, W_AREA = BK * WPITCH;
+    constexpr uint32_t RING_BYTES = PAIRED ? NXA * X_AREA + NWA * W_AREA : NST * STAGE_BYTES;
+    static_assert(!PAIRED || RING_BYTES == 160 * 1024, "the paired rings fill the LDS");
+    __shared__ __attribute__((aligned(16))) unsigned char ring[RING_BYTES];
+    __shared__ int arow_s[PAIRED ? 1 : BM];
+    __shared__ int present_s[PAIRED ? 1 : ALORA_MAX_ADAPTERS];
+    __shared__ int plist_s[PAIRED ? 1 : ALORA_MAX_ADAPTERS];
+    __shared__ int n_present_s;
+    __shared__ int64_t slot_s[PAIRED ? 1 : BM];
+    lds_byte *const ring0 = (lds_byte *)ring;
+    // token area k and weight area k of the ring(s)
+    auto xa = [&](int k) -> lds_byte * { return PAIRED ? ring0 + k * X_AREA : ring0 + k * STAGE_BYTES; };
+    auto wa = [&](int k) -> lds_byte * { return PAIRED ? ring0 + NXA * X_AREA + k * W_AREA : ring0 + k * STAGE_BYTES + W_OFF; };
+    // the areas the expand phase works in (the base prologue leaves them free)
+    lds_byte *const ex_x = xa(NXA - 1), *const ex_w = wa(NWA - 1);
+    // effective adapter per tile row; adapters present in this tile (flags, ascending list, count); cache slot per
+    // tile row (-1: no K/V write).  PAIRED: the first three in token area 4, which the main loop's first step is
+    // the first to write and which the expand and select phases, their only users, are done with by then; the
+    // slots stay in registers through the main loop and are parked behind wavefront 0's strip for the stores.
+    int *const arow = PAIRED ? (int *)(ring + 4 * X_AREA) : arow_s;
+    int *const present = PAIRED ? (int *)(ring + 4 * X_AREA + 4 * BM) : present_s;
+    int *const plist = PAIRED ? (int *)(ring + 4 * X_AREA + 4 * BM + 4 * ALORA_MAX_ADAPTERS) : plist_s;
+    int64_t *const slot_lds = PAIRED ? (int64_t *)(ring + 20 * 1024) : slot_s;
+    int &n_present = PAIRED ? *(int *)(ring + 4 * X_AREA + 4 * BM + 8 * ALORA_MAX_ADAPTERS) : n_present_s;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -218,7 +234,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                 // grouping out for itself, the first of them writes the entry's share of its results
                 const int p = (int)blockIdx.x - g.tiles8 * g.splits;
                 const int e = p / g.prep_ranges, range = p - e * g.prep_ranges;
-                int *scr = (int *)stage5;
+                unsigned char *const stage0 = ring, *const stage1 = ring + STAGE_BYTES, *const stage2 = ring + 2 * STAGE_BYTES,
+                                    *const stage3 = ring + 3 * STAGE_BYTES, *const stage4 = ring + 4 * STAGE_BYTES;
+                int *scr = (int *)(ring + 5 * STAGE_BYTES);
                 int grp, cnt;
                 const int *rows = group_small(g.prep, g.T, g.L, e, range == 0, scr, grp, cnt);
                 if (grp < 0 || grp >= g.L) { PROBE_STAMP(7); return; }   // unused entry or the rows that keep the base output
@@ -286,7 +304,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 #pragma unroll
         for (int a = 0; a < NTW; ++a) {
             const int chunk = wn * 4 * NTW + 4 * a + 2 * blk + ((s & 3) >> 1);
-            waddr[a] = W_OFF + (uint32_t)(8 * lh + j) * WPITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s & 1) << 3);
+            waddr[a] = (uint32_t)(8 * lh + j) * WPITCH + (uint32_t)((chunk ^ (j << 2)) << 4) + (uint32_t)((s & 1) << 3);
         }
     }
 
@@ -327,21 +345,42 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     const int n_base = KT - kt0;
 
     // copies of one 32-wide slice: this wavefront's four token-tile (c = 0..3) and NCW weight-tile
-    // (c = 4..) instructions
+    // (c = 4..) instructions, into the token area at LDS address sta_x and the weight area at sta_w
     auto copy = [&](int c, rsrc_t r_x, const uint32_t (&vx)[4], uint32_t sx, rsrc_t r_w, const uint32_t (&vw)[NCW],
-                    uint32_t sw, uint32_t sta) {
+                    uint32_t sw, uint32_t sta_x, uint32_t sta_w) {
         static_assert(16 * BK * 2 == LDS_COPY_STEP && RPW * WPITCH == LDS_COPY_STEP && NCW <= 4, "immediate offsets of the copies");
-        if (c == 0) set_lds_base(sta + (uint32_t)(64 * w) * (BK * 2));
-        if (c == 4) set_lds_base(sta + W_OFF + (uint32_t)(8 * w) * WPITCH);
+        if (c == 0) set_lds_base(sta_x + (uint32_t)(64 * w) * (BK * 2));
+        if (c == 4) set_lds_base(sta_w + (uint32_t)(8 * w) * WPITCH);
         if (c < 4) load_lds16(c, r_x, vx[c], sx);
         else load_lds16(c - 4, r_w, vw[c - 4], sw);
     };
+    // PAIRED: token unit u = (pair p = u / 2, row half h = u % 2) is rows 128h .. 128h+127 of slices 2p and 2p+1;
+    // this wavefront's copy j of it (j = 0..3) is row group 2w + j/2 (16 rows) of slice 2p + j%2, so that the two
+    // halves of a row's 128-byte line are requested by neighbouring instructions.  The vector offset does not
+    // depend on the slice (vxp[j/2]); row half and slice go into the scalar offset.  Units past the end repeat the
+    // last pair (into areas that are free): every step issues the same number of copies.
+    uint32_t vxp[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+        vxp[q] = lds_copy_voffset((uint32_t)((16 * (2 * w + q) + (lane >> 2)) * g.H + 8 * ((lane & 3) ^ ((lane >> 4) & 3))) * 2, 0);
+    const int n_pairs = n_base >> 1;   // (n_base is even: the hidden dimension is a multiple of 64, splits are cut in 64s)
+    auto copy_unit = [&](int j, int u, uint32_t sta_xa, uint32_t sta_xb) {
+        const int h = u & 1, pc = min(u >> 1, n_pairs - 1);
+        const uint32_t so = (uint32_t)(kt0 + 2 * pc + (j & 1)) * xstep + (uint32_t)h * 128u * (uint32_t)g.H * 2u;
+        set_lds_base(((j & 1) ? sta_xb : sta_xa) + (uint32_t)(128 * h + 16 * (2 * w + (j >> 1))) * (BK * 2));
+        load_lds16(0, rx, vxp[j >> 1], so);
+    };
+    auto copy_w = [&](int c, int s, uint32_t sta_w) {   // this wavefront's weight copy c (0 .. NCW-1) of base slice s
+        const int kb = kt0 + min(s, n_base - 1);
+        if (c == 0) set_lds_base(sta_w + (uint32_t)(8 * w) * WPITCH);
+        load_lds16(c, rw, vwb[c], kb * wstep);
+    };
     // Base slice s of this workgroup.  Slices past the end repeat the last one: every step issues
     // the same number of copies, which is what the in-order wait counts assume.
-    auto issue_base = [&](int s, uint32_t sta) {
+    auto issue_base = [&](int s, uint32_t sta_x, uint32_t sta_w) {
         const int kb = kt0 + min(s, n_base - 1);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) copy(c, rx, vxb, kb * xstep, rw, vwb, kb * wstep, sta);
+        for (int c = 0; c < NC; ++c) copy(c, rx, vxb, kb * xstep, rw, vwb, kb * wstep, sta_x, sta_w);
     };
 
     // MFMA fragments of one 16-wide k step
@@ -349,11 +388,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         return *(const __attribute__((address_space(3))) bf16x8 *)(base + ((xaddr ^ (ks << 5)) + b * 32 * BK * 2));
     };
     auto read_w = [&](const lds_byte *base, int ks, int a) { return read_w_frag(base + (waddr[a] + ks * 16 * WPITCH), WPITCH); };
-    auto load_frags = [&](const lds_byte *base, int ks, bf16x8 (&wf)[NTW], bf16x8 (&xf)[4]) {
+    auto load_frags = [&](const lds_byte *xbase, const lds_byte *wbase, int ks, bf16x8 (&wf)[NTW], bf16x8 (&xf)[4]) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) xf[b] = read_x(base, ks, b);
+        for (int b = 0; b < 4; ++b) xf[b] = read_x(xbase, ks, b);
 #pragma unroll
-        for (int a = 0; a < NTW; ++a) wf[a] = read_w(base, ks, a);
+        for (int a = 0; a < NTW; ++a) wf[a] = read_w(wbase, ks, a);
     };
     auto mfmas = [&](const bf16x8 (&wf)[NTW], const bf16x8 (&xf)[4]) {
 #pragma unroll
@@ -365,20 +404,37 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     bf16x8 wf0[NTW], xf0[4], wf1[NTW], xf1[4];
 
-    // fill the ring with the first NST-1 base slices; their latency also covers the expand phase
-    uint32_t sa[6];
+    // fill the ring with the first base slices; their latency also covers the expand phase.  PAIRED: in the
+    // order the steps -4 .. -1 of the main loop would have issued them (step s issues token unit s+4 and weight
+    // slice s+3): units 0 and 1 (slices 0, 1), weight slice 0, unit 2, weight slice 1, unit 3, weight slice 2.
+    uint32_t sax[NXA], saw[NWA];
 #pragma unroll
-    for (int u = 0; u < 6; ++u) sa[u] = lds_addr_of(st[u]);
+    for (int u = 0; u < NXA; ++u) sax[u] = lds_addr_of(xa(u));
 #pragma unroll
-    for (int u = 0; u < NST - 1; ++u) issue_base(u, sa[u]);
+    for (int u = 0; u < NWA; ++u) saw[u] = lds_addr_of(wa(u));
+    constexpr int PRO = PAIRED ? 4 * 4 + 3 * NCW : NC * (NST - 1);   // copies of the prologue per wavefront
+    if constexpr (PAIRED) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) copy_unit(j, u, sax[2 * (u >> 1)], sax[2 * (u >> 1) + 1]);
+            if (u >= 1) {
+#pragma unroll
+                for (int c = 0; c < NCW; ++c) copy_w(c, u - 1, saw[u - 1]);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < NST - 1; ++u) issue_base(u, sax[u], saw[u]);
+    }
 
     // the tile's rows have arrived (only the ring's copies may still be in flight): adapters present
     int n_exp = 0;           // expand slices ahead of the base slices
     int epa = 0;             // expand slices per adapter
     if (!SPLIT) {
-        asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a_row), "+v"(slot_row) : "n"(NC * (NST - 1)) : "memory");
+        asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a_row), "+v"(slot_row) : "n"(PRO) : "memory");
         if (a_row >= g.L) a_row = -1;   // (a workspace that holds no grouping of this batch: stay inside the tables)
-        slot_lds[tid] = slot_row;
+        if constexpr (!PAIRED) slot_lds[tid] = slot_row;
         arow[tid] = a_row;
         if (tid < ALORA_MAX_ADAPTERS) present[tid] = 0;
         __syncthreads();
@@ -424,11 +480,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
                 vw[jj] = ok ? lds_copy_voffset((uint32_t)(srow * g.N + 8 * w_chunk(jj, lane)) * 2, jj) : OOR;
             }
 #pragma unroll
-            for (int c = 0; c < NC; ++c) copy(c, rs, vx, 0, rb, vw, 0, sa[NST - 1]);
+            for (int c = 0; c < NC; ++c) copy(c, rs, vx, 0, rb, vw, 0, sax[NXA - 1], saw[NWA - 1]);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            load_frags(st_x, 0, wf0, xf0);
-            load_frags(st_x, 1, wf1, xf1);
+            load_frags(ex_x, ex_w, 0, wf0, xf0);
+            load_frags(ex_x, ex_w, 1, wf1, xf1);
             mfmas(wf0, xf0);
             mfmas(wf1, xf1);
             __syncthreads();
@@ -454,15 +510,18 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     }
 
     // ---- 3. base GEMM ---------------------------------------------------------------------
-    // step s: multiplies slice s (stage cur); fetches the first fragments of slice s+1 (stage nxt);
-    // issues the copies of slice s+NST-1 into the stage that slice s-1 occupied (tgt)
+    // step s: multiplies slice s (areas cur_x, cur_w); fetches the first fragments of slice s+1 (nxt_x, nxt_w);
+    // issues the copies of slice s+NST-1 into the areas that slice s-1 occupied (PAIRED: weight slice s+3 into the
+    // weight area of slice s-1, and token unit s+4 -- half the rows of two slices -- into the token areas
+    // tgt_xa, tgt_xb, which the slices two and one, or three and two, steps back have left)
     // Within a step the source order is the issue order: behind every MFMA one fragment read for
     // the next 16 k until they are all issued, and one copy behind every third MFMA, which keeps the
     // demand on the vector memory pipe (64 B/clk per CU) uniform.
 #if ALORA_PROBE
     const unsigned long long probe_loop_begin = __builtin_readcyclecounter();
 #endif
-    auto step = [&](int s, const lds_byte *cur, const lds_byte *nxt, uint32_t tgt) {
+    auto step = [&](int s, const lds_byte *cur_x, const lds_byte *cur_w, const lds_byte *nxt_x, const lds_byte *nxt_w,
+                    uint32_t tgt_xa, uint32_t tgt_xb, uint32_t tgt_w) {
         // this wavefront's copies of slices <= s+1 have landed (those of slices s+2 .. s+NST-2 may be
         // in flight); behind the barrier that holds for every wavefront, and all of them are done
         // reading tgt
@@ -484,16 +543,24 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             const int u = m < 5 ? m : ((m - 5) % 2 == 0 ? 5 + (m - 5) / 2 : -1);
             if (u >= 0 && u < 4 + NTW && !(ALORA_PROBE & 2)) {
                 if (half == 0) {
-                    if (u == 0) wf1[0] = read_w(cur, 1, 0);
-                    else if (u <= 4) xf1[u - 1] = read_x(cur, 1, u - 1);
-                    else wf1[u - 4] = read_w(cur, 1, u - 4);
+                    if (u == 0) wf1[0] = read_w(cur_w, 1, 0);
+                    else if (u <= 4) xf1[u - 1] = read_x(cur_x, 1, u - 1);
+                    else wf1[u - 4] = read_w(cur_w, 1, u - 4);
                 } else {
-                    if (u == 0) wf0[0] = read_w(nxt, 0, 0);
-                    else if (u <= 4) xf0[u - 1] = read_x(nxt, 0, u - 1);
-                    else wf0[u - 4] = read_w(nxt, 0, u - 4);
+                    if (u == 0) wf0[0] = read_w(nxt_w, 0, 0);
+                    else if (u <= 4) xf0[u - 1] = read_x(nxt_x, 0, u - 1);
+                    else wf0[u - 4] = read_w(nxt_w, 0, u - 4);
                 }
             }
-            if (gm % CI == 1 && gm / CI < NC && !(ALORA_PROBE & 1)) copy(gm / CI, rx, vxb, sx, rw, vwb, sw, tgt);
+            if (gm % CI == 1 && gm / CI < NC && !(ALORA_PROBE & 1)) {
+                const int c = gm / CI;
+                if constexpr (PAIRED) {
+                    if (c < 4) copy_unit(c, s + 4, tgt_xa, tgt_xb);
+                    else copy_w(c - 4, s + 3, tgt_w);
+                } else {
+                    copy(c, rx, vxb, sx, rw, vwb, sw, tgt_xa, tgt_w);
+                }
+            }
         }
         // the same order, spelled out for the instruction scheduler (MFMA, then the LDS reads of its unit)
 #pragma unroll
@@ -510,11 +577,20 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     PROBE_STAMP(2);   // expand and select done
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NC * (NST - 2)) : "memory");
     PROBE_STAMP(3);   // first slices landed
-    load_frags(st0, 0, wf0, xf0);
-    for (int s = 0; s < n_base; s += NST) {
+    load_frags(xa(0), wa(0), 0, wf0, xf0);
+    // unrolled over one period of the rings, so that every area is a compile-time address
+    constexpr int UNR = PAIRED ? 12 : NST;
+    for (int s = 0; s < n_base; s += UNR) {
 #pragma unroll
-        for (int u = 0; u < NST; ++u)
-            if (u == 0 || s + u < n_base) step(s + u, st[u], st[(u + 1) % NST], sa[(u + NST - 1) % NST]);
+        for (int u = 0; u < UNR; ++u)
+            if (u == 0 || s + u < n_base) {
+                if constexpr (PAIRED)
+                    step(s + u, xa(u % NXA), wa(u % NWA), xa((u + 1) % NXA), wa((u + 1) % NWA),
+                         sax[(u + 4 - (u & 1)) % NXA], sax[(u + 5 - (u & 1)) % NXA], saw[(u + 3) % NWA]);
+                else
+                    step(s + u, xa(u), wa(u), xa((u + 1) % NST), wa((u + 1) % NST), sax[(u + NST - 1) % NST], 0u,
+                         saw[(u + NST - 1) % NST]);
+            }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     PROBE_STAMP(4);   // main loop done
@@ -529,13 +605,18 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     // writes of four consecutive features, 16-byte reads along the row), so that global stores are
     // whole row segments: 64*NTW contiguous bytes of q_out or of one cache slot per token.
     __syncthreads();  // every wavefront has finished reading the K-slice stages
+    constexpr uint32_t STRIP_STEP = PAIRED ? 32768 : STAGE_BYTES;   // a wavefront's strip starts at w * STRIP_STEP
+    if constexpr (PAIRED && !SPLIT) {
+        slot_lds[tid] = slot_row;   // (behind wavefront 0's strip; the barrier below precedes every use)
+        __syncthreads();
+    }
     if (SPLIT) {
         // fp32 accumulators of this split, turned around through LDS like below: 16-byte writes of
         // four consecutive features, 16-byte reads along the row, row segments of 128*NTW bytes out
         constexpr int EP = 128 * NTW + 16;
         constexpr int LPR = 8 * NTW;           // lanes per row (four floats each)
         constexpr int RPI = 64 / LPR;
-        lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
+        lds_byte *strip = ring0 + w * STRIP_STEP;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 4;
         float *out = g.partial + (size_t)by * g.T * g.N;
@@ -566,7 +647,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         constexpr int EP = 128 * NTW + 16;     // strip row pitch in bytes (fp32)
         constexpr int LPR = 2 * NTW;           // lanes per row (2 x 8 features each)
         constexpr int RPI = 64 / LPR;          // rows per store instruction
-        lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
+        lds_byte *strip = ring0 + w * STRIP_STEP;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 8;         // first of the lower 8 features; the upper 8 are n + 64
         u32x2 bias4[NTW][4];
@@ -585,7 +666,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             else { region = 2; col = n - g.Nq - g.Nkv; }
         }
         // positions of the tile's rows (clamped into the tables), kept behind the last wavefront's strip
-        int *pos_lds = (int *)(st[NST - 1] + 24 * 1024);
+        int *pos_lds = (int *)(ring + 120 * 1024);
         if (tid < BM) pos_lds[tid] = m0 + tid < g.T ? min(max(g.pos[m0 + tid], 0), g.rope_positions - 1) : 0;
         __syncthreads();
         auto angles = [&](int row, f32x4 (&cs)[4]) {      // cos and sin of the lane's 8 planes at the row's position
@@ -655,7 +736,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         constexpr int EP = 64 * NTW + 16;      // strip row pitch in bytes
         constexpr int LPR = 4 * NTW;           // lanes per row (16 bytes each)
         constexpr int RPI = 64 / LPR;          // rows per store instruction
-        lds_byte *strip = w == 0 ? st0 : w == 1 ? st1 : w == 2 ? st2 : st3;
+        lds_byte *strip = ring0 + w * STRIP_STEP;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 8;
         // bias of the four consecutive features this lane holds per (feature tile, register quad):
