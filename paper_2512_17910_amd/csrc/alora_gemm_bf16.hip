@@ -20,8 +20,11 @@
 //   - global -> LDS with buffer loads that write LDS directly (no VGPR staging); the buffer
 //     descriptor's range check returns zeros for token rows past T, masked lanes get an
 //     out-of-range offset.
-//   - the K dimension runs through a ring of LDS stages, 32 k per stage: four 32 KB stages, six
-//     24 KB stages for the 128-wide tile.  While slice i is multiplied, the first fragments of
+//   - the K dimension runs through rings of LDS areas, 32 k per slice: six 24 KB stages (token
+//     slice + weight slice) for the 128-wide tile; for the 192- and 256-wide tiles six token areas
+//     and four weight areas of 16 KB, where a step's token copies cover half the rows of TWO
+//     slices so that both halves of a 128-byte line of x are asked for by neighbouring
+//     instructions (see PAIRED in the kernel).  While slice i is multiplied, the first fragments of
 //     slice i+1 are already fetched from LDS and the slices after it are in flight from memory;
 //     their copies are issued one per two or three MFMAs, which keeps the demand on the vector
 //     memory pipe (64 B/clk per CU) uniform.  One barrier per slice, placed where the MFMAs that
@@ -255,10 +258,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         const int total = g.mtiles * g.ntiles, chunk = (total + 7) >> 3;
         const int l = (bx & 7) * chunk + (bx >> 3);
         if (l >= total) return;  // grid is padded to a multiple of 8; uniform across the workgroup
-        const int panel = l / (4 * g.ntiles), rem = l - panel * 4 * g.ntiles;
-        const int pm = min(4, g.mtiles - 4 * panel);
+        // (token tiles per panel.  Measured, L2-miss reads and kernel time at T = 8192, 8192 -> 10240 / T = 4096,
+        // 4096 -> 6144: 4: 2.79 GB, 993 us / 351 MB, 180 us; 8: 2.50 GB, 993 us / 380 MB, 180 us; 2: 3.80 GB, 1019 us /
+        // 636 MB, 182 us; 16: 4.15 GB, 1016 us / 619 MB, 183 us.)
+        constexpr int PANEL = 4;
+        const int panel = l / (PANEL * g.ntiles), rem = l - panel * PANEL * g.ntiles;
+        const int pm = min(PANEL, g.mtiles - PANEL * panel);
         nt = rem / pm;
-        mt = 4 * panel + rem - nt * pm;
+        mt = PANEL * panel + rem - nt * pm;
     }
     const int m0 = mt * BM, n0 = nt * BN;
     const int wt = w & 1, wn = w >> 1;   // wave owns tokens [wt*128,+128) x features [wn*32*NTW,+32*NTW)

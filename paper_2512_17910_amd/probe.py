@@ -98,7 +98,7 @@ def run_one(bits: int, config: int, calls: int, rows: int = 0) -> None:
     loop_cycles = float(np.median(cyc[cyc > 0]))
     span = float((st[:, 6].max() - st[:, 0].min()) * 0.01)
     phases = ", ".join(f"{PHASES[i]} -> {PHASES[i + 1]}: {np.median(d[:, i]):.2f}" for i in range(6))
-    print(f"{w.name} probe {bits} ({VARIANTS.get(bits, 'experiment')}): {len(st)} workgroups, kernel span {span:.1f} us; "
+    print(f"{w.name} probe {bits} ({VARIANTS[bits]}): {len(st)} workgroups, kernel span {span:.1f} us; "
           f"main loop {loop_us:.2f} us, {loop_cycles:.0f} shader cycles -> {loop_cycles / loop_us / 1e3:.3f} GHz; "
           f"median phase times in us: {phases}", flush=True)
 
@@ -148,7 +148,7 @@ def main() -> None:
     ap.add_argument("what", choices=["build", "run", "run-one", "gaps", "mfma"])
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5, 6])
     ap.add_argument("--calls", type=int, default=30)
-    ap.add_argument("--bits", type=int, default=4, choices=sorted(VARIANTS) + [36])
+    ap.add_argument("--bits", type=int, default=4, choices=sorted(VARIANTS))
     ap.add_argument("--rows", type=int, default=0, help="run: a batch of this many rows in configuration 2's shapes instead")
     a = ap.parse_args()
     if a.what == "build":
