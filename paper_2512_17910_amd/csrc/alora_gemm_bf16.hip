@@ -38,6 +38,7 @@
 //     per-lane condition and stores are 8-byte vectors.
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 #include "alora_internal.h"
 #include "alora_group_small.h"
 #include "alora_shrink_rows.h"
@@ -746,17 +747,6 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         lds_byte *strip = ring0 + w * STRIP_STEP;
         const int er = lane / LPR, ec = lane % LPR;
         const int n = n0 + wn * 32 * NTW + ec * 8;
-        // bias of the four consecutive features this lane holds per (feature tile, register quad):
-        // part of the base output of every row, added in fp32 before the one rounding
-        u32x2 bias4[NTW][4];   // kept packed (two bf16 per register) until it is added
-#pragma unroll
-        for (int a = 0; a < NTW; ++a)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int nf = n0 + wn * 32 * NTW + a * 32 + 8 * gq + 4 * lh;
-                bias4[a][gq] = (u32x2){0u, 0u};
-                if (g.bias && nf < g.N) bias4[a][gq] = *(const u32x2 *)(g.bias + nf);
-            }
         // destination of this lane's 8 features: 0 = q_out, 1 = K cache, 2 = V cache, -1 = none
         int region = -1, col = 0;
         if (er < RPI && n < g.N) {
@@ -764,36 +754,60 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             else if (n < g.Nq + g.Nkv) { region = 1; col = n - g.Nq; }
             else { region = 2; col = n - g.Nq - g.Nkv; }
         }
+        // The epilogue is bound by the number of instructions a wavefront issues, so per stored row segment it is
+        // kept to one predicate and one 64-bit multiply-add: a lane's destination is base + index * pitch, where the
+        // index is the token row (q_out) or the row's cache slot (K, V; negative: no write), and the layer bias is
+        // only touched by calls that have one (two copies of the loop).
+        bf16_t *const dbase = (region <= 0 ? g.q : region == 1 ? g.kc : g.vc) + col;
+        const int64_t dpitch = region <= 0 ? g.Nq : g.Nkv;
+        auto rounds = [&](auto has_bias) {
+            constexpr bool BIAS = decltype(has_bias)::value;
+            // bias of the four consecutive features this lane holds per (feature tile, register quad): part of the
+            // base output of every row, added in fp32 before the one rounding; kept packed until it is added
+            u32x2 bias4[NTW][4];
+            if constexpr (BIAS) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+                for (int a = 0; a < NTW; ++a)
 #pragma unroll
-            for (int a = 0; a < NTW; ++a) {
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    f32x2 p0 = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1]};
-                    f32x2 p1 = {acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
-                    p0 += (f32x2){__uint_as_float(bias4[a][gq].x << 16), __uint_as_float(bias4[a][gq].x & 0xffff0000u)};
-                    p1 += (f32x2){__uint_as_float(bias4[a][gq].y << 16), __uint_as_float(bias4[a][gq].y & 0xffff0000u)};
-                    u32x2 v;
-                    v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2));
-                    v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2));
-                    *(__attribute__((address_space(3))) u32x2 *)(strip + li * EP + (a * 32 + 8 * gq + 4 * lh) * 2) = v;
-                }
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int nf = n0 + wn * 32 * NTW + a * 32 + 8 * gq + 4 * lh;
+                        bias4[a][gq] = (u32x2){0u, 0u};
+                        if (nf < g.N) bias4[a][gq] = *(const u32x2 *)(g.bias + nf);
+                    }
             }
 #pragma unroll
-            for (int i = 0; i < (32 + RPI - 1) / RPI; ++i) {
-                const int r = i * RPI + er;
-                const int row = wt * 128 + b * 32 + r;
-                if (region < 0 || r >= 32 || m0 + row >= g.T) continue;
-                const u32x4 v = *(const __attribute__((address_space(3))) u32x4 *)(strip + r * EP + ec * 16);
-                if (region == 0) {
-                    *(u32x4 *)(g.q + (size_t)(m0 + row) * g.Nq + col) = v;
-                } else {
-                    const int64_t sl = slot_lds[row];
-                    if (sl >= 0) *(u32x4 *)((region == 1 ? g.kc : g.vc) + (size_t)sl * g.Nkv + col) = v;
+            for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                for (int a = 0; a < NTW; ++a) {
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        f32x2 p0 = {acc[a][b][4 * gq + 0], acc[a][b][4 * gq + 1]};
+                        f32x2 p1 = {acc[a][b][4 * gq + 2], acc[a][b][4 * gq + 3]};
+                        if constexpr (BIAS) {
+                            p0 += (f32x2){__uint_as_float(bias4[a][gq].x << 16), __uint_as_float(bias4[a][gq].x & 0xffff0000u)};
+                            p1 += (f32x2){__uint_as_float(bias4[a][gq].y << 16), __uint_as_float(bias4[a][gq].y & 0xffff0000u)};
+                        }
+                        u32x2 v;
+                        v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(p0, bf16x2));
+                        v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(p1, bf16x2));
+                        *(__attribute__((address_space(3))) u32x2 *)(strip + li * EP + (a * 32 + 8 * gq + 4 * lh) * 2) = v;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < (32 + RPI - 1) / RPI; ++i) {
+                    const int r = i * RPI + er;
+                    const int row = min(wt * 128 + b * 32 + r, BM - 1);   // (r can pass 31 in the last iteration: masked below)
+                    const int64_t idx = region == 0 ? (int64_t)(m0 + row) : slot_lds[row];
+                    const bool ok = (region >= 0) & (r < 32) & (m0 + row < g.T) & (idx >= 0);
+                    if (ok) {
+                        const u32x4 v = *(const __attribute__((address_space(3))) u32x4 *)(strip + r * EP + ec * 16);
+                        *(u32x4 *)(dbase + idx * dpitch) = v;
+                    }
                 }
             }
-        }
+        };
+        if (g.bias) rounds(std::true_type{});
+        else rounds(std::false_type{});
     }
 #if ALORA_PROBE
     PROBE_STAMP(5);   // stores issued
