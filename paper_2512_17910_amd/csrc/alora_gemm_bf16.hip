@@ -372,11 +372,20 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
     for (int q = 0; q < 2; ++q)
         vxp[q] = lds_copy_voffset((uint32_t)((16 * (2 * w + q) + (lane >> 2)) * g.H + 8 * ((lane & 3) ^ ((lane >> 4) & 3))) * 2, 0);
     const int n_pairs = n_base >> 1;   // (n_base is even: the hidden dimension is a multiple of 64, splits are cut in 64s)
-    auto copy_unit = [&](int j, int u, uint32_t sta_xa, uint32_t sta_xb) {
-        const int h = u & 1, pc = min(u >> 1, n_pairs - 1);
-        const uint32_t so = (uint32_t)(kt0 + 2 * pc + (j & 1)) * xstep + (uint32_t)h * 128u * (uint32_t)g.H * 2u;
+    // One descriptor per row half, each ending at the tile's last valid row: the scalar offset of a buffer load is
+    // not part of its range check, so the row half must not travel there (rows past T would be read, and past
+    // the end of x in the last tile); the scalar offset only moves along a row.
+    const int xm0 = (ALORA_PROBE & 8) ? 0 : m0, xrows = (ALORA_PROBE & 8) ? min(g.T, BM) : rows_valid;
+    // (readfirstlane: the clamps would otherwise be computed by a vector instruction, and the descriptor with them)
+    const int xrows0 = __builtin_amdgcn_readfirstlane(min(xrows, 128)), xrows1 = __builtin_amdgcn_readfirstlane(max(xrows - 128, 0));
+    const rsrc_t rxh0 = make_rsrc_copy(g.x + (size_t)xm0 * g.H, (uint32_t)xrows0 * g.H * 2);
+    const rsrc_t rxh1 = make_rsrc_copy(g.x + (size_t)(xm0 + 128) * g.H, (uint32_t)xrows1 * g.H * 2);
+    auto copy_unit = [&](int j, int u, int h, uint32_t sta_xa, uint32_t sta_xb) {   // h = u % 2, a constant at every call
+        const int pc = min(u >> 1, n_pairs - 1);
+        const uint32_t so = (uint32_t)(kt0 + 2 * pc + (j & 1)) * xstep;
         set_lds_base(((j & 1) ? sta_xb : sta_xa) + (uint32_t)(128 * h + 16 * (2 * w + (j >> 1))) * (BK * 2));
-        load_lds16(0, rx, vxp[j >> 1], so);
+        if (h) load_lds16(0, rxh1, vxp[j >> 1], so);
+        else load_lds16(0, rxh0, vxp[j >> 1], so);
     };
     auto copy_w = [&](int c, int s, uint32_t sta_w) {   // this wavefront's weight copy c (0 .. NCW-1) of base slice s
         const int kb = kt0 + min(s, n_base - 1);
@@ -425,7 +434,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) copy_unit(j, u, sax[2 * (u >> 1)], sax[2 * (u >> 1) + 1]);
+            for (int j = 0; j < 4; ++j) copy_unit(j, u, u & 1, sax[2 * (u >> 1)], sax[2 * (u >> 1) + 1]);
             if (u >= 1) {
 #pragma unroll
                 for (int c = 0; c < NCW; ++c) copy_w(c, u - 1, saw[u - 1]);
@@ -528,8 +537,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 #if ALORA_PROBE
     const unsigned long long probe_loop_begin = __builtin_readcyclecounter();
 #endif
-    auto step = [&](int s, const lds_byte *cur_x, const lds_byte *cur_w, const lds_byte *nxt_x, const lds_byte *nxt_w,
-                    uint32_t tgt_xa, uint32_t tgt_xb, uint32_t tgt_w) {
+    auto step = [&](int s, int par, const lds_byte *cur_x, const lds_byte *cur_w, const lds_byte *nxt_x, const lds_byte *nxt_w,
+                    uint32_t tgt_xa, uint32_t tgt_xb, uint32_t tgt_w) {   // par = s % 2, a constant at every call
         // this wavefront's copies of slices <= s+1 have landed (those of slices s+2 .. s+NST-2 may be
         // in flight); behind the barrier that holds for every wavefront, and all of them are done
         // reading tgt
@@ -563,7 +572,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
             if (gm % CI == 1 && gm / CI < NC && !(ALORA_PROBE & 1)) {
                 const int c = gm / CI;
                 if constexpr (PAIRED) {
-                    if (c < 4) copy_unit(c, s + 4, tgt_xa, tgt_xb);
+                    if (c < 4) copy_unit(c, s + 4, par, tgt_xa, tgt_xb);
                     else copy_w(c - 4, s + 3, tgt_w);
                 } else {
                     copy(c, rx, vxb, sx, rw, vwb, sw, tgt_xa, tgt_w);
@@ -593,10 +602,10 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
         for (int u = 0; u < UNR; ++u)
             if (u == 0 || s + u < n_base) {
                 if constexpr (PAIRED)
-                    step(s + u, xa(u % NXA), wa(u % NWA), xa((u + 1) % NXA), wa((u + 1) % NWA),
+                    step(s + u, u & 1, xa(u % NXA), wa(u % NWA), xa((u + 1) % NXA), wa((u + 1) % NWA),
                          sax[(u + 4 - (u & 1)) % NXA], sax[(u + 5 - (u & 1)) % NXA], saw[(u + 3) % NWA]);
                 else
-                    step(s + u, xa(u), wa(u), xa((u + 1) % NST), wa((u + 1) % NST), sax[(u + NST - 1) % NST], 0u,
+                    step(s + u, 0, xa(u), wa(u), xa((u + 1) % NST), wa((u + 1) % NST), sax[(u + NST - 1) % NST], 0u,
                          saw[(u + NST - 1) % NST]);
             }
     }
