@@ -5,7 +5,7 @@
 //   1. fetch the tile's rows' effective adapters (the grouping step's classification, App. B mask)
 //      and cache slots; list the adapters its adapted rows use
 //   2. expand first: for each such adapter a, accumulate [S_hi | S_lo](rows of a, else 0) . [B_a ; B_a]
-//      32 k at a time through the one LDS stage the base prologue leaves free, then zero the
+//      32 k at a time through the LDS areas the base prologue leaves free, then zero the
 //      accumulators of rows that are not adapted (a select, not a multiply: adapter data never
 //      reaches a base row)
 //   3. base GEMM over the hidden dimension: rows that are not adapted see exactly the
@@ -473,7 +473,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void alora_gemm_bf16_kernel(GemmAr
 
     PROBE_STAMP(1);   // ring prologue issued, the tile's rows known
     // ---- 2. expand first, then select ------------------------------------------------------
-    // One slice at a time through the last stage (few slices, not pipelined): 32 k of
+    // One slice at a time through the areas the prologue leaves free (few slices, not pipelined): 32 k of
     // [S_hi | S_lo] for the rows of adapter a (zeros elsewhere) against the matching rows of [B_a ; B_a].
     if (!SPLIT && n_exp > 0) {
         for (int e = 0; e < n_exp; ++e) {
